@@ -1,0 +1,171 @@
+/*
+ * longgen_attn.h — C ABI of liblonggen_attn.so
+ *
+ * Causal sparse attention for the "efficient layers" of the LongGen hybrid
+ * model (arxiv 2410.01485): attention-sink + sliding-window attention and
+ * blockwise strided sparse attention (paper Section 3.1, paragraph "Different
+ * KV-Reduced Attention Strategies"; settings in Section 4.1), as a fused
+ * block-skipping kernel for prefill forward and backward (Section 3.2) and a
+ * bandwidth-bound decode kernel over the rolling-buffer KV cache (Section 3.2,
+ * second paragraph).  Hand-written HIP for gfx950; one GPU.
+ *
+ * ---------------------------------------------------------------------------
+ * THE MASK (integer-only; every entry point uses exactly this predicate)
+ * ---------------------------------------------------------------------------
+ * i = query position, j = key position, both 0-based in the same index space.
+ *   b  = max(block, 1)            granularity of the pattern in tokens
+ *   qb = i / b,  kb = j / b       block indices (integer division)
+ *   sb = sink / b, wb = window / b   (exact when block > 1: enforced)
+ *
+ *   live(i,j) :=  j <= i  &&  (  kb < sb                              sink
+ *                             || qb - kb < wb                         local window (own block included)
+ *                             || (stride > 0 && kb % stride == stride-1)   strided block columns
+ *                             )
+ *
+ * block <= 1, stride == 0  =>  token-exact sink + sliding window:
+ *        j <= i && (j < sink || i - j < window)      (exactly `window` keys incl. the query itself)
+ * block == 64, sink == 64, window == 2048            the paper's AttnSink setting (Section 4.1)
+ * block == 64, stride == 64                          the paper's BlockSparse setting (Section 4.1)
+ * The strided columns are ABSOLUTE block indices (the same for every query and
+ * every head — Section 3.1 criterion "static access of position"), which is
+ * what lets the KV cache keep one block in every `stride` (Section 4.1).
+ * The residue (last block of each group of `stride`) is this library's
+ * convention; the paper does not state one.
+ *
+ * ---------------------------------------------------------------------------
+ * Conventions common to all calls
+ * ---------------------------------------------------------------------------
+ * Pointers q/k/v/out/dout/dq/dk/dv/lse/workspace/caches are DEVICE pointers
+ * (hipMalloc'ed or PyTorch-owned), 16-byte aligned, dense row-major with the
+ * head dimension D innermost and no strides:
+ *     prefill  q,out,dout,dq : [B, Hq,  N, D]      k,v,dk,dv : [B, Hkv, N, D]
+ *              lse           : [B, Hq,  N]  float32, natural log of the sum of
+ *                              exp(scaled scores) over the live keys of a row
+ *     decode   q,out : [B, Hq, D]   k_cache,v_cache : [B, Hkv, sink+window, D]
+ *              lse   : [B, Hq] float32
+ * Element type of q/k/v/out/dout/dq/dk/dv/caches is `dtype` (lg_dtype);
+ * accumulation and softmax are always float32.
+ * GQA: query head hq reads kv head hq / (Hq/Hkv)  (consecutive query heads
+ * share a kv head; Llama-2-70B, Section 4.1).  dk/dv of a kv head are the sum
+ * over its Hq/Hkv query heads.
+ * scale <= 0 selects 1/sqrt(D).
+ * Ownership: the caller owns every buffer.  The library allocates nothing,
+ * frees nothing, never synchronises, and enqueues all work on `hip_stream`
+ * (a hipStream_t passed as void*; NULL = the default stream).  Outputs are
+ * fully overwritten.  Scratch memory comes from the caller through `workspace`
+ * (size from the matching *_workspace_bytes call; contents need not be
+ * initialised and are undefined afterwards).
+ * Errors: every call returns an lg_status.  All argument checks run before
+ * the first HIP call, so they behave the same on a host without a GPU.
+ *   LG_ERR_NULL         a required pointer is NULL (lse may be NULL in fwd and
+ *                       decode: then it is not written)
+ *   LG_ERR_INVALID_ARG  B,Hq,Hkv,N < 1; Hq % Hkv != 0; sink < 0; window < 1
+ *                       (so every row has at least one live key); block < 0;
+ *                       stride < 0; block > 1 with sink % block != 0 or
+ *                       window % block != 0; a pointer not 16-byte aligned;
+ *                       B*H*N*D beyond 2^40 elements
+ *   LG_ERR_UNSUPPORTED  D not in {64, 128}; dtype not in lg_dtype; decode with
+ *                       stride > 0 or block > 1; Hq/Hkv > 16 in decode
+ *   LG_ERR_WORKSPACE    workspace NULL or smaller than *_workspace_bytes
+ *   LG_ERR_LAUNCH       the HIP runtime reported an error at launch (no GPU,
+ *                       wrong architecture, ...)
+ * Any N >= 1 works (ragged tails are masked), not only multiples of a tile.
+ */
+#ifndef LONGGEN_ATTN_H_
+#define LONGGEN_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LG_OK = 0,
+  LG_ERR_NULL = 1,
+  LG_ERR_INVALID_ARG = 2,
+  LG_ERR_UNSUPPORTED = 3,
+  LG_ERR_WORKSPACE = 4,
+  LG_ERR_LAUNCH = 5
+} lg_status;
+
+typedef enum { LG_F32 = 0, LG_BF16 = 1 } lg_dtype;
+
+/* Static, never-freed description of a status code. */
+const char* lg_status_str(int status);
+
+/*
+ * Prefill forward (Section 3.2, first paragraph: a FlashAttention-style fused
+ * kernel that never loads key blocks whose mask is zero).
+ *   out[b,hq,i,:] = sum_j P_ij v[b,hk,j,:],  P_ij = exp(scale*<q_i,k_j> - lse_i)
+ *   over the keys j with live(i,j);  lse_i = ln sum_j exp(scale*<q_i,k_j>).
+ * out has the dtype of q (float32 results rounded to nearest-even for bf16).
+ */
+int lg_sparse_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                       int B, int Hq, int Hkv, int N, int D,
+                       int sink, int window, int block, int stride,
+                       int dtype, float scale, void* hip_stream);
+
+/*
+ * Backward of lg_sparse_attn_fwd (Section 3.2: masked blocks are skipped in the
+ * backward step as well; Table 1 counts forward and backward FLOPs).
+ * Inputs: q,k,v, the forward's out and lse, and dout = dLoss/dout.
+ *   Delta_i = <dout_i, out_i>;   dP_ij = <dout_i, v_j>;   dS_ij = P_ij (dP_ij - Delta_i)
+ *   dq_i = scale * sum_j dS_ij k_j;   dk_j = scale * sum_i dS_ij q_i;   dv_j = sum_i P_ij dout_i
+ * (sums over live pairs only; dk/dv also summed over the query heads of a kv head).
+ * workspace holds Delta (float32 [B,Hq,N]) and any float32 partial sums.
+ */
+size_t lg_sparse_attn_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                          int sink, int window, int block, int stride, int dtype);
+int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int N, int D,
+                       int sink, int window, int block, int stride,
+                       int dtype, float scale, void* hip_stream);
+
+/*
+ * Decode over the reduced KV cache (Section 3.2, second paragraph: loading the
+ * KV cache is the bottleneck; the attention-sink variant keeps the window in a
+ * rolling buffer).  One query per (b,hq): the token at position N-1 of a
+ * context of N tokens, whose own k/v is already in the cache.
+ * Cache slot map: token p lives in slot p when p < sink, otherwise in slot
+ * sink + ((p - sink) % window).  The first min(N, sink+window) slots are valid;
+ * they hold exactly the keys j with live(N-1, j), so the result equals row N-1
+ * of lg_sparse_attn_fwd on the whole context.  Token-granular pattern only
+ * (block <= 1, stride == 0).
+ * workspace holds float32 partial results of the split over cache slots.
+ */
+size_t lg_sparse_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                             int sink, int window, int dtype);
+int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
+                          void* workspace, size_t workspace_bytes,
+                          int B, int Hq, int Hkv, int N, int D,
+                          int sink, int window, int block, int stride,
+                          int dtype, float scale, void* hip_stream);
+
+/*
+ * Host-only view of the block-skipping tile scheduler (Section 3.2: the mask is
+ * kept in compressed-sparse-row form, O(N) memory; it is static for all heads).
+ * Writes, in CSR form, the list of live kernel tiles the device code walks:
+ *   transposed == 0: rows are query tiles, columns key tiles (forward, dq);
+ *   transposed == 1: rows are key tiles, columns query tiles (dk/dv).
+ * tq/tk receive the kernel tile sizes used for `dtype`.  row_ptr has rows+1
+ * entries; col_idx/kind have row_ptr[rows] entries; kind is 1 when every
+ * (i,j) of the tile is live (no masking needed) and 0 when the predicate must
+ * be applied per element.  All output pointers are HOST pointers; cap is the
+ * capacity of col_idx/kind in entries and row_cap that of row_ptr; *needed
+ * always receives the number of live tiles and *rows the number of rows, and
+ * nothing is written past a capacity (call once with cap = 0 to size).
+ * Runs the same source the kernels compile (no GPU needed).
+ */
+int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dtype, int transposed,
+                      int* tq, int* tk, int32_t* row_ptr, size_t row_cap,
+                      int32_t* col_idx, uint8_t* kind, size_t cap,
+                      size_t* rows, size_t* needed);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LONGGEN_ATTN_H_ */
