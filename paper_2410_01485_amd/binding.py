@@ -1,0 +1,155 @@
+"""ctypes binding of liblonggen_attn.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on a HIP device (contiguous, dense layouts of
+include/longgen_attn.h); their data pointers and the current stream are handed to the
+library.  Nothing here computes: a missing or unbuilt library is an error, never a fallback.
+"""
+import ctypes
+import os
+
+LG_F32, LG_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblonggen_attn.so")
+_lib = None
+
+_vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+
+
+class LgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2410_01485_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("liblonggen_attn.so is not built: run `python -m paper_2410_01485_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.lg_status_str.argtypes = [_i]
+        L.lg_status_str.restype = ctypes.c_char_p
+        L.lg_sparse_attn_fwd.argtypes = [_vp] * 5 + [_i] * 9 + [_i, _f, _vp]
+        L.lg_sparse_attn_fwd.restype = _i
+        L.lg_sparse_attn_bwd_workspace_bytes.argtypes = [_i] * 10
+        L.lg_sparse_attn_bwd_workspace_bytes.restype = _sz
+        L.lg_sparse_attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
+        L.lg_sparse_attn_bwd.restype = _i
+        L.lg_sparse_attn_decode_workspace_bytes.argtypes = [_i] * 8
+        L.lg_sparse_attn_decode_workspace_bytes.restype = _sz
+        L.lg_sparse_attn_decode.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
+        L.lg_sparse_attn_decode.restype = _i
+        L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
+                                                   _vp, _vp, _sz, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
+        L.lg_debug_tile_map.restype = _i
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().lg_status_str(int(status)).decode()
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return LG_F32
+    if t.dtype == torch.bfloat16:
+        return LG_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(t):
+    import torch
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _check(t, *shape):
+    if not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError("expected a contiguous device tensor of shape %s, got %s" % (shape, tuple(t.shape)))
+
+
+def lg_sparse_attn_fwd(q, k, v, out, lse, sink, window, block=1, stride=0, scale=0.0):
+    """out, lse <- sparse attention forward of q [B,Hq,N,D], k,v [B,Hkv,N,D]; lse may be None."""
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    _check(q, B, Hq, N, D), _check(k, B, Hkv, N, D), _check(v, B, Hkv, N, D), _check(out, B, Hq, N, D)
+    if lse is not None:
+        _check(lse, B, Hq, N)
+    st = lib().lg_sparse_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, Hq, Hkv, N, D,
+                                  sink, window, block, stride, _dtype_code(q), scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_fwd")
+
+
+def bwd_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, dtype):
+    return int(lib().lg_sparse_attn_bwd_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, dtype))
+
+
+def lg_sparse_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink, window, block=1, stride=0,
+                       scale=0.0):
+    """dq, dk, dv <- backward of lg_sparse_attn_fwd; workspace is a uint8 device tensor."""
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    for t in (q, out, dout, dq):
+        _check(t, B, Hq, N, D)
+    for t in (k, v, dk, dv):
+        _check(t, B, Hkv, N, D)
+    _check(lse, B, Hq, N)
+    st = lib().lg_sparse_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                  _ptr(dk), _ptr(dv), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
+                                  _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_bwd")
+
+
+def decode_workspace_bytes(B, Hq, Hkv, N, D, sink, window, dtype):
+    return int(lib().lg_sparse_attn_decode_workspace_bytes(B, Hq, Hkv, N, D, sink, window, dtype))
+
+
+def lg_sparse_attn_decode(q, k_cache, v_cache, out, lse, workspace, N, sink, window, block=1, stride=0,
+                          scale=0.0):
+    """out, lse <- one-token attention of q [B,Hq,D] over caches [B,Hkv,sink+window,D]."""
+    B, Hq, D = q.shape
+    Hkv = k_cache.shape[1]
+    _check(k_cache, B, Hkv, sink + window, D), _check(v_cache, B, Hkv, sink + window, D), _check(out, B, Hq, D)
+    if lse is not None:
+        _check(lse, B, Hq)
+    st = lib().lg_sparse_attn_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
+                                     _ptr(workspace),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
+                                     _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_decode")
+
+
+def lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed):
+    """Host-only: (tq, tk, row_ptr, col_idx, kind) numpy arrays of the scheduler's live tiles."""
+    import numpy as np
+    tq, tk = _i(0), _i(0)
+    rows, need = _sz(0), _sz(0)
+    st = lib().lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed, ctypes.byref(tq),
+                                 ctypes.byref(tk), None, 0, None, None, 0, ctypes.byref(rows), ctypes.byref(need))
+    if st != 0:
+        raise LgError(st, "lg_debug_tile_map")
+    row_ptr = np.zeros(rows.value + 1, dtype=np.int32)
+    col = np.zeros(max(need.value, 1), dtype=np.int32)
+    kind = np.zeros(max(need.value, 1), dtype=np.uint8)
+    st = lib().lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed, ctypes.byref(tq),
+                                 ctypes.byref(tk), row_ptr.ctypes.data, row_ptr.size, col.ctypes.data,
+                                 kind.ctypes.data, need.value, ctypes.byref(rows), ctypes.byref(need))
+    if st != 0:
+        raise LgError(st, "lg_debug_tile_map")
+    return tq.value, tk.value, row_ptr, col[:need.value], kind[:need.value]

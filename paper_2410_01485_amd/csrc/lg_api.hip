@@ -1,0 +1,197 @@
+// lg_api.hip — the extern "C" boundary of liblonggen_attn.so: argument checks
+// (all before the first HIP call), dtype dispatch, and the host view of the tile
+// scheduler.  See include/longgen_attn.h for the contract of every entry point.
+#include <math.h>
+
+#include "../../include/longgen_attn.h"
+#include "lg_kernels.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_common(int B, int Hq, int Hkv, int N, int D, int sink, int window, int block, int stride,
+                 int dtype) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || N < 1) return LG_ERR_INVALID_ARG;
+  if (Hq % Hkv != 0) return LG_ERR_INVALID_ARG;
+  if (sink < 0 || window < 1 || block < 0 || stride < 0) return LG_ERR_INVALID_ARG;
+  if (block > 1 && (sink % block != 0 || window % block != 0)) return LG_ERR_INVALID_ARG;
+  if (D < 1) return LG_ERR_INVALID_ARG;
+  const double elems = (double)B * (double)Hq * (double)N * (double)D;
+  if (elems > 1099511627776.0) return LG_ERR_INVALID_ARG;  // 2^40
+  if (D != 64 && D != 128) return LG_ERR_UNSUPPORTED;
+  if (dtype != LG_F32 && dtype != LG_BF16) return LG_ERR_UNSUPPORTED;
+  return LG_OK;
+}
+
+LgShape make_shape(int B, int Hq, int Hkv, int N, int D, float scale) {
+  LgShape sh;
+  sh.B = B;
+  sh.Hq = Hq;
+  sh.Hkv = Hkv;
+  sh.N = N;
+  sh.D = D;
+  sh.scale = scale > 0.0f ? scale : 1.0f / sqrtf((float)D);
+  return sh;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lg_status_str(int status) {
+  switch (status) {
+    case LG_OK: return "ok";
+    case LG_ERR_NULL: return "a required pointer is NULL";
+    case LG_ERR_INVALID_ARG: return "invalid argument";
+    case LG_ERR_UNSUPPORTED: return "unsupported head dimension, dtype or pattern";
+    case LG_ERR_WORKSPACE: return "workspace missing or too small";
+    case LG_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int lg_sparse_attn_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                       int B, int Hq, int Hkv, int N, int D,
+                       int sink, int window, int block, int stride,
+                       int dtype, float scale, void* hip_stream) {
+  if (!q || !k || !v || !out) return LG_ERR_NULL;
+  int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+    return LG_ERR_INVALID_ARG;
+  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
+  const LgMask m = lg_make_mask(N, sink, window, block, stride);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (dtype == LG_F32)
+      ? lg_launch_fwd_f32((const float*)q, (const float*)k, (const float*)v, (float*)out, lse, sh, m, s)
+      : lg_launch_fwd_bf16(q, k, v, out, lse, sh, m, s);
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+size_t lg_sparse_attn_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                          int sink, int window, int block, int stride, int dtype) {
+  if (check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype) != LG_OK) return 0;
+  return lg_bwd_workspace_bytes(make_shape(B, Hq, Hkv, N, D, 0.0f),
+                                lg_make_mask(N, sink, window, block, stride), dtype);
+}
+
+int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int N, int D,
+                       int sink, int window, int block, int stride,
+                       int dtype, float scale, void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return LG_ERR_NULL;
+  int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LG_ERR_INVALID_ARG;
+  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
+  const LgMask m = lg_make_mask(N, sink, window, block, stride);
+  if (!workspace || workspace_bytes < lg_bwd_workspace_bytes(sh, m, dtype)) return LG_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (dtype == LG_F32)
+      ? lg_launch_bwd_f32((const float*)q, (const float*)k, (const float*)v, (const float*)out, lse,
+                          (const float*)dout, (float*)dq, (float*)dk, (float*)dv, workspace, sh, m, s)
+      : lg_launch_bwd_bf16(q, k, v, out, lse, dout, dq, dk, dv, workspace, sh, m, s);
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+static int check_decode(int B, int Hq, int Hkv, int N, int D, int sink, int window, int block,
+                        int stride, int dtype) {
+  int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  if (stride > 0 || block > 1) return LG_ERR_UNSUPPORTED;
+  if (Hq / Hkv > 16) return LG_ERR_UNSUPPORTED;
+  if ((double)sink + (double)window > 1073741824.0) return LG_ERR_INVALID_ARG;
+  return LG_OK;
+}
+
+size_t lg_sparse_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                             int sink, int window, int dtype) {
+  if (check_decode(B, Hq, Hkv, N, D, sink, window, 1, 0, dtype) != LG_OK) return 0;
+  const int C = sink + window;
+  return lg_decode_workspace_bytes(B, Hq, Hkv, D, N < C ? N : C);
+}
+
+int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
+                          void* workspace, size_t workspace_bytes,
+                          int B, int Hq, int Hkv, int N, int D,
+                          int sink, int window, int block, int stride,
+                          int dtype, float scale, void* hip_stream) {
+  if (!q || !k_cache || !v_cache || !out) return LG_ERR_NULL;
+  int st = check_decode(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      !aligned16(lse) || !aligned16(workspace))
+    return LG_ERR_INVALID_ARG;
+  const int C = sink + window;
+  const int valid = N < C ? N : C;
+  const size_t need = lg_decode_workspace_bytes(B, Hq, Hkv, D, valid);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LG_ERR_WORKSPACE;
+  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
+  hipError_t e = lg_launch_decode(q, k_cache, v_cache, out, lse, workspace, B, Hq, Hkv, C, valid, D,
+                                  dtype, sh.scale, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dtype, int transposed,
+                      int* tq, int* tk, int32_t* row_ptr, size_t row_cap,
+                      int32_t* col_idx, uint8_t* kind, size_t cap,
+                      size_t* rows, size_t* needed) {
+  if (!tq || !tk || !rows || !needed) return LG_ERR_NULL;
+  int st = check_common(1, 1, 1, N, 64, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  const LgMask m = lg_make_mask(N, sink, window, block, stride);
+  int Tq, Tk;
+  if (dtype == LG_F32) {
+    Tq = transposed ? LG_F32_BTQ : LG_F32_TQ;
+    Tk = transposed ? LG_F32_BTK : LG_F32_TK;
+  } else {
+    Tq = transposed ? LG_BF16_BTQ : LG_BF16_TQ;
+    Tk = transposed ? LG_BF16_BTK : LG_BF16_TK;
+  }
+  *tq = Tq;
+  *tk = Tk;
+  size_t n = 0, r = 0;
+  auto emit = [&](int col, int kd) {
+    if (n < cap) {
+      if (col_idx) col_idx[n] = col;
+      if (kind) kind[n] = (uint8_t)(kd == LG_TILE_FULL);
+    }
+    ++n;
+  };
+  auto mark_row = [&]() {
+    if (row_ptr && r < row_cap) row_ptr[r] = (int32_t)n;
+    ++r;
+  };
+  if (!transposed) {
+    const int nq = (N + Tq - 1) / Tq;
+    for (int u = 0; u < nq; ++u) {
+      mark_row();
+      const int q0 = u * Tq, q1 = (q0 + Tq - 1 < N - 1) ? q0 + Tq - 1 : N - 1;
+      for (int t = lg_next_ktile(m, q0, q1, Tk, -1); t >= 0; t = lg_next_ktile(m, q0, q1, Tk, t))
+        emit(t, lg_tile_kind(m, q0, q1, t * Tk, t * Tk + Tk - 1));
+    }
+  } else {
+    const int nk = (N + Tk - 1) / Tk;
+    for (int t = 0; t < nk; ++t) {
+      mark_row();
+      const int k0 = t * Tk, k1 = (k0 + Tk - 1 < N - 1) ? k0 + Tk - 1 : N - 1;
+      int lo, hi;
+      lg_qtile_range(m, k0, k1, Tq, &lo, &hi);
+      for (int u = lo; u <= hi; ++u) {
+        const int q0 = u * Tq, q1 = (q0 + Tq - 1 < N - 1) ? q0 + Tq - 1 : N - 1;
+        emit(u, lg_tile_kind(m, q0, q1, k0, t * Tk + Tk - 1));
+      }
+    }
+  }
+  if (row_ptr && r < row_cap) row_ptr[r] = (int32_t)n;
+  *rows = r;
+  *needed = n;
+  return LG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,290 @@
+// lg_decode.hip — decode over the sink + rolling-window KV cache (paper Section 3.2,
+// second paragraph: at inference the bottleneck is loading the KV cache as fast as
+// possible; the attention-sink variant keeps the window in a rolling buffer).
+//
+// One query per (b, hq); every valid cache slot is read exactly once.  The work is
+// pure HBM streaming (about one flop per byte), so it runs on vector ALUs with
+// 16-byte coalesced loads: LPR consecutive lanes read one key row, a wave reads
+// 64/LPR consecutive rows per load, and U loads of K and of V are in flight per
+// lane.  The slots of one (b, hkv) are split over `splits` workgroups so the chip
+// is filled even for small batches; a second tiny kernel merges the partial
+// (max, sum, accumulator) triples.  All query heads of a kv head are served by the
+// same pass over K/V (GQA).
+#include <hip/hip_bf16.h>
+
+#include "../../include/longgen_attn.h"
+#include "lg_kernels.h"
+
+namespace {
+
+constexpr int WAVES = 4;
+constexpr int U = 4;  // key rows per lane group per iteration
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over a group of LPR consecutive lanes (LPR in {8,16,32}); every lane of the
+// group receives the total.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp_f<0xB1>(x);  // quad_perm [1,0,3,2]
+  x += dpp_f<0x4E>(x);  // quad_perm [2,3,0,1]
+  if constexpr (LPR == 8) {
+    x += dpp_f<0x141>(x);  // row_half_mirror: the other quad of the 8
+  } else {
+    x += dpp_f<0x124>(x);  // row_ror:4
+    x += dpp_f<0x128>(x);  // row_ror:8
+    if constexpr (LPR == 32) x += __shfl_xor(x, 16);
+  }
+  return x;
+}
+
+template <typename T, int E>
+struct Frag;  // E elements of T loaded as one 16-byte vector, widened to float
+template <>
+struct Frag<float, 4> {
+  __device__ static void load(const void* p, float* f) {
+    const float4 x = *reinterpret_cast<const float4*>(p);
+    f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
+  }
+};
+template <>
+struct Frag<__hip_bfloat16, 8> {
+  __device__ static void load(const void* p, float* f) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      f[2 * t] = __uint_as_float(w[t] << 16);
+      f[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+    }
+  }
+};
+
+__device__ __forceinline__ void store_out(float* p, float x) { *p = x; }
+__device__ __forceinline__ void store_out(__hip_bfloat16* p, float x) { *p = __float2bfloat16(x); }
+
+// Partial record in the workspace, per (b, hq, split): D accumulators, max, sum
+// (max and running values are in the log2 domain: score * scale * log2(e)).
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict__ q,
+                                                            const T* __restrict__ kc,
+                                                            const T* __restrict__ vc,
+                                                            T* __restrict__ out, float* __restrict__ lse,
+                                                            float* __restrict__ ws, int Hq, int Hkv,
+                                                            int C, int valid, int chunk, int splits,
+                                                            float scale_log2e) {
+  constexpr int E = 16 / sizeof(T);      // elements per 16-byte lane load
+  constexpr int LPR = D / E;             // lanes per key row
+  constexpr int KPW = 64 / LPR;          // key rows per wave per load
+  constexpr int GROUPS = WAVES * KPW;    // lane groups per workgroup
+  __shared__ float sM[WAVES][GT], sL[WAVES][GT];
+  __shared__ float sO[WAVES][GT][D];
+
+  const int G = Hq / Hkv;
+  const int ngc = (G + GT - 1) / GT;  // chunks of GT query heads per kv head
+  const int split = blockIdx.x;
+  const int hk = blockIdx.y / ngc, gc = blockIdx.y % ngc;
+  const int b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = wave * KPW + lane / LPR;
+  const int dl = (lane % LPR) * E;  // first head-dim element of this lane
+  const int s0 = split * chunk;
+  const int s1 = min(valid, s0 + chunk);
+
+  float qf[GT][E], o[GT][E], mrun[GT], lrun[GT];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    const int hq = min(hk * G + gc * GT + g, Hq - 1);
+    Frag<T, E>::load(q + ((size_t)b * Hq + hq) * D + dl, qf[g]);
+    mrun[g] = -INFINITY;
+    lrun[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      qf[g][e] *= scale_log2e;
+      o[g][e] = 0.f;
+    }
+  }
+
+  const T* kbase = kc + ((size_t)b * Hkv + hk) * C * D + dl;
+  const T* vbase = vc + ((size_t)b * Hkv + hk) * C * D + dl;
+  for (int base = s0; base < s1; base += GROUPS * U) {
+    float kf[U][E], vf[U][E];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int slot = base + u * GROUPS + grp;
+      ok[u] = slot < s1;
+      const size_t off = (size_t)(ok[u] ? slot : s1 - 1) * D;
+      Frag<T, E>::load(kbase + off, kf[u]);
+      Frag<T, E>::load(vbase + off, vf[u]);
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float s[U];
+      float mb = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float a = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) a = fmaf(qf[g][e], kf[u][e], a);
+        a = group_sum<LPR>(a);
+        s[u] = ok[u] ? a : -INFINITY;
+        mb = fmaxf(mb, s[u]);
+      }
+      const float mnew = fmaxf(mrun[g], mb);
+      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+      const float alpha = exp2f(mrun[g] - msafe);
+      mrun[g] = mnew;
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[g][e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = exp2f(s[u] - msafe);
+        psum += p;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = fmaf(p, vf[u][e], o[g][e]);
+      }
+      lrun[g] = lrun[g] * alpha + psum;
+    }
+  }
+
+  // merge the KPW lane groups of the wave (lanes LPR apart hold the same dims)
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    float mall = mrun[g];
+#pragma unroll
+    for (int x = LPR; x < 64; x <<= 1) mall = fmaxf(mall, __shfl_xor(mall, x));
+    const float msafe = (mall == -INFINITY) ? 0.f : mall;
+    const float w = exp2f(mrun[g] - msafe);
+    float l = lrun[g] * w;
+#pragma unroll
+    for (int x = LPR; x < 64; x <<= 1) l += __shfl_xor(l, x);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      float a = o[g][e] * w;
+#pragma unroll
+      for (int x = LPR; x < 64; x <<= 1) a += __shfl_xor(a, x);
+      o[g][e] = a;
+    }
+    if (lane < LPR) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) sO[wave][g][dl + e] = o[g][e];
+      if (lane == 0) {
+        sM[wave][g] = mall;
+        sL[wave][g] = l;
+      }
+    }
+  }
+  __syncthreads();
+
+  // merge the waves; GT*D outputs spread over the workgroup
+  for (int idx = threadIdx.x; idx < GT * D; idx += WAVES * 64) {
+    const int g = idx / D, d = idx % D;
+    const int hq = hk * G + gc * GT + g;
+    if (gc * GT + g >= G) continue;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, sM[w][g]);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float f = exp2f(sM[w][g] - M);
+      L += sL[w][g] * f;
+      acc += sO[w][g][d] * f;
+    }
+    const size_t row = (size_t)b * Hq + hq;
+    if (splits == 1) {
+      store_out(out + row * D + d, acc / L);
+      if (lse != nullptr && d == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
+    } else {
+      float* rec = ws + (row * splits + split) * (D + 2);
+      rec[d] = acc;
+      if (d == 0) {
+        rec[D] = M;
+        rec[D + 1] = L;
+      }
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(const float* __restrict__ ws,
+                                                         T* __restrict__ out, float* __restrict__ lse,
+                                                         int splits) {
+  const size_t row = blockIdx.x;
+  const int d = threadIdx.x;
+  const float* rec = ws + row * splits * (D + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, rec[s * (D + 2) + D]);
+  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float f = exp2f(rec[s * (D + 2) + D] - M);
+    L += rec[s * (D + 2) + D + 1] * f;
+    acc += rec[s * (D + 2) + d] * f;
+  }
+  store_out(out + row * D + d, acc / L);
+  if (lse != nullptr && d == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
+}
+
+template <typename T, int D>
+hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out, float* lse, void* ws,
+                        int B, int Hq, int Hkv, int C, int valid, float scale, hipStream_t s) {
+  const int G = Hq / Hkv;
+  const int splits = lg_decode_splits(B, Hkv, valid);
+  const int chunk = (valid + splits - 1) / splits;
+  const float sl2 = scale * 1.44269504088896340736f;
+  const T* tq = (const T*)q;
+  const T* tk = (const T*)kc;
+  const T* tv = (const T*)vc;
+  T* to = (T*)out;
+  float* fws = (float*)ws;
+#define LG_DECODE_LAUNCH(GT)                                                                     \
+  decode_kernel<T, D, GT><<<dim3(splits, Hkv*((G + GT - 1) / GT), B), WAVES * 64, 0, s>>>(       \
+      tq, tk, tv, to, lse, fws, Hq, Hkv, C, valid, chunk, splits, sl2)
+  if (G == 1) LG_DECODE_LAUNCH(1);
+  else if (G == 2) LG_DECODE_LAUNCH(2);
+  else if (G <= 4) LG_DECODE_LAUNCH(4);
+  else LG_DECODE_LAUNCH(8);
+#undef LG_DECODE_LAUNCH
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  decode_merge_kernel<T, D><<<dim3(B * Hq), D, 0, s>>>(fws, to, lse, splits);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Enough workgroups to fill 256 CUs several times over, but at least 256 slots each
+// and never an empty split.
+int lg_decode_splits(int B, int Hkv, int valid) {
+  const long long pairs = (long long)B * Hkv;
+  long long want = (4096 + pairs - 1) / pairs;
+  const long long cap = (valid + 255) / 256;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  const int chunk = (int)((valid + want - 1) / want);
+  return (valid + chunk - 1) / chunk;
+}
+
+size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid) {
+  const int splits = lg_decode_splits(B, Hkv, valid);
+  if (splits == 1) return 0;
+  return (size_t)B * Hq * splits * (D + 2) * sizeof(float);
+}
+
+hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                            void* ws, int B, int Hq, int Hkv, int C, int valid, int D, int dtype,
+                            float scale, hipStream_t s) {
+  if (dtype == LG_F32) {
+    return D == 64 ? launch_typed<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
+                   : launch_typed<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
+  }
+  return D == 64
+      ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
+      : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
+}

@@ -1,0 +1,51 @@
+// lg_kernels.h — internal interface between the C ABI (lg_api.hip) and the kernel
+// translation units.  Tile sizes live here because the host-side tile map
+// (lg_debug_tile_map) must enumerate exactly the tiles the kernels walk.
+#ifndef LG_KERNELS_H_
+#define LG_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lg_mask.h"
+
+// Kernel tile sizes (query rows x keys per step).  Independent of the pattern's
+// `block`: they never change results, only which tiles count as PARTIAL.
+enum {
+  LG_F32_TQ = 64, LG_F32_TK = 64,        // float32 kernels, forward / dq order
+  LG_F32_BTQ = 64, LG_F32_BTK = 64,      // float32 dk/dv kernel (key-tile major)
+  LG_BF16_TQ = 128, LG_BF16_TK = 64,     // bf16 MFMA forward and dq kernels
+  LG_BF16_BTQ = 64, LG_BF16_BTK = 128    // bf16 MFMA dk/dv kernel (key-tile major)
+};
+
+struct LgShape {
+  int B, Hq, Hkv, N, D;
+  float scale;  // already resolved (> 0)
+};
+
+// Each launcher enqueues on `s` and returns hipGetLastError().
+hipError_t lg_launch_fwd_f32(const float* q, const float* k, const float* v, float* out, float* lse,
+                             const LgShape& sh, const LgMask& m, hipStream_t s);
+hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void* out, float* lse,
+                              const LgShape& sh, const LgMask& m, hipStream_t s);
+
+// Delta_i = <dout_i, out_i> for rows = B*Hq*N rows of D elements of either dtype.
+hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, long long rows, int D,
+                           int dtype, hipStream_t s);
+size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype);
+hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, const float* out,
+                             const float* lse, const float* dout, float* dq, float* dk, float* dv,
+                             void* ws, const LgShape& sh, const LgMask& m, hipStream_t s);
+hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const void* out,
+                              const float* lse, const void* dout, void* dq, void* dk, void* dv,
+                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s);
+
+// Decode: C = sink + window cache slots per (b, hkv), `valid` of them in use.
+int lg_decode_splits(int B, int Hkv, int valid);
+size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid);
+hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                            void* ws, int B, int Hq, int Hkv, int C, int valid, int D,
+                            int dtype, float scale, hipStream_t s);
+
+#endif  // LG_KERNELS_H_

@@ -1,0 +1,96 @@
+"""GPU parity: lg_sparse_attn_bwd (through the C ABI) against the fp64 oracle, element by element.
+
+The GPU backward consumes the GPU forward's own out / lse (as a training step does); the oracle
+computes its forward in fp64 itself."""
+import numpy as np
+import pytest
+import torch
+
+import lg_synth
+import paper_2410_01485_amd as lg
+from gpu_util import DEV, TOL_OUT, TOL_REL, assert_close, f32np
+from oracle import lg_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def run_fwd_bwd(q, k, v, g, sink, window, block=1, stride=0, scale=0.0):
+    qd, kd, vd, gd = (x.to(DEV) for x in (q, k, v, g))
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    code = lg.LG_BF16 if q.dtype == torch.bfloat16 else lg.LG_F32
+    out = torch.empty_like(qd)
+    lse = torch.empty(B, Hq, N, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd(qd, kd, vd, out, lse, sink, window, block, stride, scale)
+    need = lg.bwd_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, code)
+    assert need >= B * Hq * N * 4
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    dq = torch.full_like(qd, float("nan"))
+    dk = torch.full_like(kd, float("nan"))
+    dv = torch.full_like(vd, float("nan"))
+    lg.lg_sparse_attn_bwd(qd, kd, vd, out, lse, gd, dq, dk, dv, ws, sink, window, block, stride, scale)
+    torch.cuda.synchronize()
+    return dq, dk, dv
+
+
+def check_bwd(B, Hq, Hkv, N, D, sink, window, block=1, stride=0, dtype=torch.bfloat16, seed=1, q_mul=1.0,
+              scale=0.0, by_tensor_max=False):
+    q, k, v, g = lg_synth.prefill_inputs(B, Hq, Hkv, N, D, seed, dtype, with_dout=True, q_mul=q_mul)
+    dq, dk, dv = run_fwd_bwd(q, k, v, g, sink, window, block, stride, scale)
+    w = O.bwd(f32np(q), f32np(k), f32np(v), f32np(g), sink, window, block, stride, scale if scale > 0 else None)
+    tag = "bwd B%d Hq%d Hkv%d N%d D%d s%d w%d b%d st%d %s" % (B, Hq, Hkv, N, D, sink, window, block, stride, dtype)
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        assert_close(f32np(got), w[name], TOL_OUT[dtype], TOL_REL[dtype], tag + " " + name, by_tensor_max)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_sink_window_ragged_gqa(D, dtype):
+    check_bwd(2, 4, 2, 700, D, 64, 200, dtype=dtype, seed=2)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N,sink,window,block,stride", [
+    (1, 0, 1, 1, 0), (33, 4, 8, 1, 0), (257, 0, 50, 1, 0), (500, 600, 3, 1, 0), (640, 5, 1000, 1, 0),
+    (1024, 64, 192, 64, 8), (1000, 48, 96, 48, 3), (900, 0, 16, 16, 1), (777, 3, 10, 1, 7),
+])
+def test_patterns_and_edges(dtype, N, sink, window, block, stride):
+    check_bwd(1, 2, 1, N, 128, sink, window, block, stride, dtype=dtype, seed=3)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_peaked_scores_and_custom_scale(dtype):
+    check_bwd(1, 2, 2, 600, 128, 16, 100, dtype=dtype, seed=4, q_mul=4.0, by_tensor_max=True)
+    check_bwd(1, 4, 1, 300, 64, 16, 100, dtype=dtype, seed=5, scale=0.3, by_tensor_max=True)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_masked_keys_get_exactly_zero_gradient(dtype):
+    # upstream gradient only on a few rows: keys dead for all of them get dk = dv = 0 exactly,
+    # and every other query row gets dq = 0 exactly
+    N, D, sink, window = 1500, 128, 64, 256
+    q, k, v, g = lg_synth.prefill_inputs(1, 2, 2, N, D, 7, dtype, with_dout=True)
+    rows = np.arange(1300, 1400)
+    g2 = torch.zeros_like(g)
+    g2[:, :, rows] = g[:, :, rows]
+    dq, dk, dv = run_fwd_bwd(q, k, v, g2, sink, window)
+    m = O.mask(N, sink, window)
+    dead = np.where(~m[rows].any(axis=0))[0]
+    assert len(dead) > 1000
+    assert (f32np(dk)[:, :, dead] == 0).all() and (f32np(dv)[:, :, dead] == 0).all()
+    other = np.setdiff1d(np.arange(N), rows)
+    assert (f32np(dq)[:, :, other] == 0).all()
+    assert np.abs(f32np(dq)[:, :, rows]).sum() > 0
+
+
+def test_bwd_deterministic():
+    q, k, v, g = lg_synth.prefill_inputs(1, 4, 2, 900, 128, 9, torch.bfloat16, with_dout=True)
+    a = run_fwd_bwd(q, k, v, g, 64, 300)
+    b = run_fwd_bwd(q, k, v, g, 64, 300)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_config3_shape_reduced_n_all_heads():
+    # config 3's heads, head dim, sink and window at a sequence the oracle finishes: N = 6144
+    check_bwd(1, 32, 32, 6144, 128, 64, 4096, dtype=torch.bfloat16, seed=20241004)

@@ -1,0 +1,112 @@
+"""GPU parity: lg_sparse_attn_fwd (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import lg_synth
+import paper_2410_01485_amd as lg
+from gpu_util import DEV, TOL_LSE, TOL_OUT, TOL_REL, assert_close, check_fwd, f32np, run_fwd
+from oracle import lg_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_fp32_sink_window():
+    # B1 H1 N1024 D64 fp32, sink 16, window 128: max abs error <= 1e-4
+    check_fwd(1, 1, 1, 1024, 64, 16, 128, dtype=torch.float32, seed=20241002)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_sink_window_ragged_gqa(D, dtype):
+    check_fwd(2, 4, 2, 700, D, 64, 200, dtype=dtype, seed=2)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N,sink,window,block,stride", [
+    (1, 0, 1, 1, 0), (33, 4, 8, 1, 0), (257, 0, 50, 1, 0), (500, 600, 3, 1, 0), (640, 5, 1000, 1, 0),
+    (1024, 64, 192, 64, 8), (1000, 48, 96, 48, 3), (900, 0, 16, 16, 1), (777, 3, 10, 1, 7),
+])
+def test_patterns_and_edges(dtype, N, sink, window, block, stride):
+    check_fwd(1, 2, 1, N, 128, sink, window, block, stride, dtype=dtype, seed=3)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_peaked_scores_and_custom_scale(dtype):
+    check_fwd(1, 2, 2, 600, 128, 16, 100, dtype=dtype, seed=4, q_mul=8.0)
+    check_fwd(1, 2, 2, 300, 64, 16, 100, dtype=dtype, seed=5, scale=0.3)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_zero_queries_closed_form(dtype):
+    # Q = 0: lse_i = ln(number of live keys), out_i = mean of the live value rows
+    N, D, sink, window = 600, 128, 7, 90
+    _, k, v = lg_synth.prefill_inputs(1, 1, 1, N, D, 6, dtype)
+    q = torch.zeros(1, 1, N, D, dtype=dtype)
+    out, lse = run_fwd(q, k, v, sink, window)
+    cnt = np.array([min(i + 1, window) + min(sink, max(0, i - window + 1)) for i in range(N)], dtype=np.float64)
+    assert_close(f32np(lse)[0, 0], np.log(cnt), 1e-5, None, "lse closed form")
+    m = O.mask(N, sink, window).astype(np.float64)
+    mean_v = (m @ f32np(v)[0, 0].astype(np.float64)) / cnt[:, None]
+    assert_close(f32np(out)[0, 0], mean_v, TOL_OUT[dtype], None, "uniform average")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dead_keys_do_not_matter(dtype):
+    # keys that are dead for every probed row may hold any finite garbage: results are bit-identical
+    N, D, sink, window = 1500, 128, 64, 256
+    q, k, v = lg_synth.prefill_inputs(1, 2, 2, N, D, 7, dtype)
+    out, lse = run_fwd(q, k, v, sink, window)
+    rows = np.arange(1280, 1500)
+    m = O.mask(N, sink, window)
+    dead = torch.as_tensor(np.where(~m[rows].any(axis=0))[0])
+    assert len(dead) > 500
+    k2, v2 = k.clone(), v.clone()
+    k2[:, :, dead] = 3.0e4
+    v2[:, :, dead] = -7.0e4
+    out2, lse2 = run_fwd(q, k2, v2, sink, window)
+    assert torch.equal(out[:, :, rows], out2[:, :, rows]) and torch.equal(lse[:, :, rows], lse2[:, :, rows])
+
+
+def test_lse_optional_and_deterministic():
+    q, k, v = lg_synth.prefill_inputs(1, 2, 1, 500, 128, 8, torch.bfloat16)
+    a, la = run_fwd(q, k, v, 8, 64)
+    b, _ = run_fwd(q, k, v, 8, 64, want_lse=False)
+    c, lc = run_fwd(q, k, v, 8, 64)
+    assert torch.equal(a, b) and torch.equal(a, c) and torch.equal(la, lc)
+
+
+def sampled_full_size(Hq, Hkv, N, sink, window, block, stride, seed, heads, row_starts, nrows=48):
+    """Full-size launch (the benchmark's configuration); the oracle recomputes sampled rows."""
+    D = 128
+    q, k, v = lg_synth.prefill_inputs(1, Hq, Hkv, N, D, seed, torch.bfloat16, device=DEV)
+    out = torch.empty_like(q)
+    lse = torch.empty(1, Hq, N, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window, block, stride)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    G = Hq // Hkv
+    for hq in heads:
+        qh = f32np(q[:, hq:hq + 1])
+        kh = f32np(k[:, hq // G:hq // G + 1])
+        vh = f32np(v[:, hq // G:hq // G + 1])
+        for r0 in row_starts:
+            r0 = min(r0, N - nrows)
+            wo, wl = O.fwd(qh, kh, vh, sink, window, block, stride, rows=(r0, r0 + nrows))
+            tag = "full-size N%d head %d rows %d.." % (N, hq, r0)
+            assert_close(f32np(out[0, hq, r0:r0 + nrows]), wo[0, 0, r0:r0 + nrows], TOL_OUT[torch.bfloat16],
+                         TOL_REL[torch.bfloat16], tag + " out")
+            assert_close(f32np(lse[0, hq, r0:r0 + nrows]), wl[0, 0, r0:r0 + nrows], TOL_LSE[torch.bfloat16],
+                         None, tag + " lse")
+
+
+def test_config2_full_size_sampled():
+    # Llama-2-7B shape, block-strided: 32 heads, N=32768, 64-token blocks, own+2 preceding, sink block, every 8th
+    sampled_full_size(32, 32, 32768, 64, 192, 64, 8, 20241003, heads=[0, 13, 31],
+                      row_starts=[0, 200, 4090, 16384 + 100, 32768])
+
+
+def test_config4_full_size_sampled():
+    # Llama-2-70B shape, GQA 64/8, N=131072, sink 64 + window 4096
+    sampled_full_size(64, 8, 131072, 64, 4096, 1, 0, 20241005, heads=[0, 7, 8, 37, 63],
+                      row_starts=[0, 4000, 4150, 65536 + 77, 131072])

@@ -1,0 +1,90 @@
+"""The block-skipping tile scheduler, bit-exact against brute force over the oracle's predicate.
+
+lg_debug_tile_map runs on the host the same source the kernels compile; the brute-force side
+builds the dense mask with the oracle and reduces it per tile.  No GPU needed."""
+import numpy as np
+import pytest
+
+import paper_2410_01485_amd as lg
+from oracle import lg_oracle as O
+
+
+def brute_tiles(mask, Tq, Tk, transposed):
+    N = mask.shape[0]
+    nq, nk = -(-N // Tq), -(-N // Tk)
+    rows = []
+    for a in range(nk if transposed else nq):
+        row = []
+        for c in range(nq if transposed else nk):
+            u, t = (c, a) if transposed else (a, c)
+            sub = mask[u * Tq:(u + 1) * Tq, t * Tk:(t + 1) * Tk]
+            if sub.any():
+                # FULL: every pair of the nominal Tq x Tk tile exists and is live
+                full = bool(sub.all()) and sub.shape == (min(Tq, N - u * Tq), Tk)
+                row.append((c, int(full)))
+        rows.append(row)
+    return rows
+
+
+def check(N, sink, window, block, stride, dtype, transposed):
+    tq, tk, rp, ci, kd = lg.lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed)
+    want = brute_tiles(O.mask(N, sink, window, block, stride), tq, tk, transposed)
+    assert len(rp) == len(want) + 1
+    got = [[(int(ci[x]), int(kd[x])) for x in range(rp[r], rp[r + 1])] for r in range(len(want))]
+    assert got == want, (N, sink, window, block, stride, dtype, transposed)
+
+
+CASES = [
+    (1, 0, 1, 1, 0), (63, 0, 1, 1, 0), (64, 5, 7, 1, 0), (65, 16, 128, 1, 0), (200, 0, 64, 1, 0),
+    (1024, 16, 128, 1, 0), (777, 64, 130, 1, 0), (513, 100, 1, 1, 0), (600, 700, 5, 1, 0),
+    (600, 3, 900, 1, 0), (1000, 0, 300, 1, 3), (999, 7, 20, 1, 64), (1024, 64, 192, 64, 8),
+    (1500, 64, 64, 64, 4), (1100, 48, 96, 48, 3), (900, 32, 32, 16, 5), (1111, 0, 8, 8, 1),
+    (1000, 40, 120, 40, 2), (2048, 256, 512, 128, 4), (1300, 96, 192, 96, 7), (700, 0, 24, 24, 1000),
+]
+
+
+@pytest.mark.parametrize("dtype", [lg.LG_F32, lg.LG_BF16])
+@pytest.mark.parametrize("transposed", [0, 1])
+def test_tile_map_equals_brute_force(dtype, transposed):
+    for c in CASES:
+        check(*c, dtype, transposed)
+
+
+def test_tile_map_randomised():
+    rng = np.random.default_rng(7)
+    for _ in range(60):
+        b = int(rng.choice([1, 1, 2, 3, 16, 64, 100]))
+        N = int(rng.integers(1, 1400))
+        sink = int(rng.integers(0, 6)) * b * int(rng.choice([1, 3]))
+        window = int(rng.integers(1, 12)) * b * int(rng.choice([1, 5]))
+        stride = int(rng.choice([0, 0, 1, 2, 3, 8, 50]))
+        for tr in (0, 1):
+            check(N, sink, window, b, stride, int(rng.integers(0, 2)), tr)
+
+
+def test_live_tile_totals_of_benchmark_configs():
+    # config 2: 64-token blocks, tile = one block of keys: live key blocks per 64-row query block
+    # summed over the rows of the bf16 kernel's query tiles
+    tq, tk, rp, ci, kd = lg.lg_debug_tile_map(32768, 64, 192, 64, 8, lg.LG_BF16, 0)
+    assert tk == 64
+    # every live 64x64 block is covered by exactly one (query tile, key tile) pair per 64-row slice
+    m_blocks = 0
+    per_qtile = tq // 64
+    nb = 32768 // 64
+    live_blocks = set()
+    for qb in range(nb):
+        for kb in range(qb + 1):
+            if kb < 1 or qb - kb < 3 or kb % 8 == 7:
+                live_blocks.add((qb, kb))
+    assert len(live_blocks) == 18044
+    covered = set()
+    for u in range(len(rp) - 1):
+        for x in range(rp[u], rp[u + 1]):
+            for s in range(per_qtile):
+                covered.add((u * per_qtile + s, int(ci[x])))
+    assert live_blocks <= covered
+    # config 3: sink 64 + window 4096 at 128K: each query tile sees at most 1 sink + window + edge tiles
+    tq, tk, rp, ci, kd = lg.lg_debug_tile_map(131072, 64, 4096, 1, 0, lg.LG_BF16, 0)
+    per_row = np.diff(rp)
+    assert per_row.max() <= 1 + (4096 + tq) // tk + 1
+    assert int(per_row[-1]) == 1 + (4096 + tq - 1 + tk - 1) // tk
