@@ -126,6 +126,19 @@ int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* 
                        int dtype, float scale, void* hip_stream);
 
 /*
+ * Measurement aid (benchmarks only): lg_sparse_attn_bwd with each of its three kernels
+ * bracketed by HIP events on hip_stream.  Synchronises the stream and writes the kernel
+ * durations in milliseconds to the HOST array kernel_ms[3] = {Delta pre-pass, dq kernel,
+ * dk/dv kernel}.  Creates and destroys its events; results are those of lg_sparse_attn_bwd.
+ */
+int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes,
+                           int B, int Hq, int Hkv, int N, int D,
+                           int sink, int window, int block, int stride,
+                           int dtype, float scale, void* hip_stream, float* kernel_ms);
+
+/*
  * Decode over the reduced KV cache (Section 3.2, second paragraph: loading the
  * KV cache is the bottleneck; the attention-sink variant keeps the window in a
  * rolling buffer).  One query per (b,hq): the token at position N-1 of a

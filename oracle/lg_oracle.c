@@ -77,11 +77,34 @@ static double dot_fd(const float* a, const float* b, long D) {
   return s;
 }
 
+/* One query row: scores over the live keys, their maximum, the normaliser, lse and
+ * the output row.  s is scratch of N doubles.
+ *   s_j = scale <q_i,k_j> for live j;  m = max s;  l = sum exp(s_j - m)
+ *   lse_i = m + ln l;  out_i = sum_j exp(s_j - m)/l * v_j */
+static void forward_row(const float* qh, const float* kh, const float* vh, long i, long D,
+                        long sink, long window, long block, long stride, double scale,
+                        double* s, double* out_row, double* lse_i) {
+  double m = -INFINITY;
+  for (long j = 0; j <= i; ++j) {
+    if (!lgo_live(i, j, sink, window, block, stride)) continue;
+    s[j] = scale * dot_fd(qh + i * D, kh + j * D, D);
+    if (s[j] > m) m = s[j];
+  }
+  double l = 0.0;
+  for (long j = 0; j <= i; ++j)
+    if (lgo_live(i, j, sink, window, block, stride)) l += exp(s[j] - m);
+  *lse_i = m + log(l);
+  for (long d = 0; d < D; ++d) out_row[d] = 0.0;
+  for (long j = 0; j <= i; ++j) {
+    if (!lgo_live(i, j, sink, window, block, stride)) continue;
+    double p = exp(s[j] - m) / l;
+    for (long d = 0; d < D; ++d) out_row[d] += p * (double)vh[j * D + d];
+  }
+}
+
 /*
  * Forward for rows [i0, i1) of every (b, hq).  out [B,Hq,N,D] and lse [B,Hq,N]
  * are double; rows outside [i0,i1) are left untouched.
- *   s_j = scale <q_i,k_j> for live j;  m = max s;  l = sum exp(s_j - m)
- *   lse_i = m + ln l;  out_i = sum_j exp(s_j - m)/l * v_j
  */
 void lgo_fwd(const float* q, const float* k, const float* v, double* out, double* lse,
              long B, long Hq, long Hkv, long N, long D,
@@ -99,53 +122,67 @@ void lgo_fwd(const float* q, const float* k, const float* v, double* out, double
       {
         double* s = (double*)malloc(sizeof(double) * (size_t)N);
 #pragma omp for schedule(dynamic, 16)
-        for (long i = i0; i < i1; ++i) {
-          double m = -INFINITY;
-          for (long j = 0; j <= i; ++j) {
-            if (!lgo_live(i, j, sink, window, block, stride)) continue;
-            s[j] = scale * dot_fd(qh + i * D, kh + j * D, D);
-            if (s[j] > m) m = s[j];
-          }
-          double l = 0.0;
-          for (long j = 0; j <= i; ++j)
-            if (lgo_live(i, j, sink, window, block, stride)) l += exp(s[j] - m);
-          lh[i] = m + log(l);
-          for (long d = 0; d < D; ++d) oh[i * D + d] = 0.0;
-          for (long j = 0; j <= i; ++j) {
-            if (!lgo_live(i, j, sink, window, block, stride)) continue;
-            double p = exp(s[j] - m) / l;
-            for (long d = 0; d < D; ++d) oh[i * D + d] += p * (double)vh[j * D + d];
-          }
-        }
+        for (long i = i0; i < i1; ++i)
+          forward_row(qh, kh, vh, i, D, sink, window, block, stride, scale, s, oh + i * D, lh + i);
         free(s);
       }
     }
 }
 
 /*
- * Backward.  Computes its own fp64 forward (out, lse) first, then
+ * Backward, restricted to query rows [i0,i1) for dq and to keys [j0,j1) for dk/dv
+ * (the full ranges give the whole gradient).  Computes its own fp64 forward (out,
+ * lse) for every row it needs — the rows of [i0,i1) and every row that sees a key of
+ * [j0,j1) — then
  *   Delta_i = <dout_i, out_i>;  P_ij = exp(s_ij - lse_i);  dP_ij = <dout_i, v_j>
  *   dS_ij = P_ij (dP_ij - Delta_i)
  *   dq_i = scale sum_j dS_ij k_j          (pass over rows)
  *   dk_j = scale sum_i dS_ij q_i,  dv_j = sum_i P_ij dout_i   (pass over keys,
  *          summed over the Hq/Hkv query heads that read kv head hk)
- * dq [B,Hq,N,D], dk,dv [B,Hkv,N,D] double, fully written.
- * out_opt / lse_opt (may be NULL) receive the fp64 forward.
+ * dq [B,Hq,N,D], dk,dv [B,Hkv,N,D] double; only the requested rows / keys are
+ * written.  out_opt / lse_opt (may be NULL) receive the fp64 forward of the rows
+ * that were needed (other rows untouched).
  */
-void lgo_bwd(const float* q, const float* k, const float* v, const float* dout,
-             double* dq, double* dk, double* dv, double* out_opt, double* lse_opt,
-             long B, long Hq, long Hkv, long N, long D,
-             long sink, long window, long block, long stride, double scale) {
+void lgo_bwd_part(const float* q, const float* k, const float* v, const float* dout,
+                  double* dq, double* dk, double* dv, double* out_opt, double* lse_opt,
+                  long B, long Hq, long Hkv, long N, long D,
+                  long sink, long window, long block, long stride, double scale,
+                  long i0, long i1, long j0, long j1) {
   long G = Hq / Hkv;
   double* out = out_opt ? out_opt : (double*)malloc(sizeof(double) * (size_t)(B * Hq * N * D));
   double* lse = lse_opt ? lse_opt : (double*)malloc(sizeof(double) * (size_t)(B * Hq * N));
   double* delta = (double*)malloc(sizeof(double) * (size_t)(B * Hq * N));
-  lgo_fwd(q, k, v, out, lse, B, Hq, Hkv, N, D, sink, window, block, stride, scale, 0, N);
-  for (long r = 0; r < B * Hq * N; ++r) {
-    double a = 0.0;
-    for (long d = 0; d < D; ++d) a += (double)dout[r * D + d] * out[r * D + d];
-    delta[r] = a;
+  unsigned char* need = (unsigned char*)malloc((size_t)N);
+#pragma omp parallel for schedule(dynamic, 64)
+  for (long i = 0; i < N; ++i) {
+    need[i] = (unsigned char)(i >= i0 && i < i1);
+    for (long j = j0; j < j1 && j <= i && !need[i]; ++j)
+      if (lgo_live(i, j, sink, window, block, stride)) need[i] = 1;
   }
+  for (long b = 0; b < B; ++b)
+    for (long hq = 0; hq < Hq; ++hq) {
+      long hk = hq / G;
+      const float* qh = q + (b * Hq + hq) * N * D;
+      const float* gh = dout + (b * Hq + hq) * N * D;
+      const float* kh = k + (b * Hkv + hk) * N * D;
+      const float* vh = v + (b * Hkv + hk) * N * D;
+      double* oh = out + (b * Hq + hq) * N * D;
+      double* lh = lse + (b * Hq + hq) * N;
+      double* dh = delta + (b * Hq + hq) * N;
+#pragma omp parallel
+      {
+        double* s = (double*)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 16)
+        for (long i = 0; i < N; ++i) {
+          if (!need[i]) continue;
+          forward_row(qh, kh, vh, i, D, sink, window, block, stride, scale, s, oh + i * D, lh + i);
+          double a = 0.0;
+          for (long d = 0; d < D; ++d) a += (double)gh[i * D + d] * oh[i * D + d];
+          dh[i] = a;
+        }
+        free(s);
+      }
+    }
   /* dq: one row at a time */
   for (long b = 0; b < B; ++b)
     for (long hq = 0; hq < Hq; ++hq) {
@@ -158,7 +195,7 @@ void lgo_bwd(const float* q, const float* k, const float* v, const float* dout,
       const double* dh = delta + (b * Hq + hq) * N;
       double* dqh = dq + (b * Hq + hq) * N * D;
 #pragma omp parallel for schedule(dynamic, 16)
-      for (long i = 0; i < N; ++i) {
+      for (long i = i0; i < i1; ++i) {
         for (long d = 0; d < D; ++d) dqh[i * D + d] = 0.0;
         for (long j = 0; j <= i; ++j) {
           if (!lgo_live(i, j, sink, window, block, stride)) continue;
@@ -176,7 +213,7 @@ void lgo_bwd(const float* q, const float* k, const float* v, const float* dout,
       double* dkh = dk + (b * Hkv + hk) * N * D;
       double* dvh = dv + (b * Hkv + hk) * N * D;
 #pragma omp parallel for schedule(dynamic, 16)
-      for (long j = 0; j < N; ++j) {
+      for (long j = j0; j < j1; ++j) {
         for (long d = 0; d < D; ++d) dkh[j * D + d] = dvh[j * D + d] = 0.0;
         for (long g = 0; g < G; ++g) {
           long hq = hk * G + g;
@@ -196,9 +233,19 @@ void lgo_bwd(const float* q, const float* k, const float* v, const float* dout,
         }
       }
     }
+  free(need);
   free(delta);
   if (!out_opt) free(out);
   if (!lse_opt) free(lse);
+}
+
+/* The whole gradient. */
+void lgo_bwd(const float* q, const float* k, const float* v, const float* dout,
+             double* dq, double* dk, double* dv, double* out_opt, double* lse_opt,
+             long B, long Hq, long Hkv, long N, long D,
+             long sink, long window, long block, long stride, double scale) {
+  lgo_bwd_part(q, k, v, dout, dq, dk, dv, out_opt, lse_opt, B, Hq, Hkv, N, D, sink, window, block, stride,
+               scale, 0, N, 0, N);
 }
 
 /*

@@ -49,6 +49,8 @@ def _load():
         L.lgo_fwd.restype = None
         L.lgo_bwd.argtypes = [fp, fp, fp, fp, dp, dp, dp, dp, dp] + [lng] * 9 + [dbl]
         L.lgo_bwd.restype = None
+        L.lgo_bwd_part.argtypes = [fp, fp, fp, fp, dp, dp, dp, dp, dp] + [lng] * 9 + [dbl] + [lng] * 4
+        L.lgo_bwd_part.restype = None
         L.lgo_decode.argtypes = [fp, fp, fp, dp, dp] + [lng] * 7 + [dbl]
         L.lgo_decode.restype = None
         _lib = L
@@ -109,8 +111,11 @@ def fwd(q, k, v, sink, window, block=1, stride=0, scale=None, rows=None):
     return out, lse
 
 
-def bwd(q, k, v, dout, sink, window, block=1, stride=0, scale=None):
-    """-> dict(dq, dk, dv, out, lse) float64; out/lse are the oracle's own forward."""
+def bwd(q, k, v, dout, sink, window, block=1, stride=0, scale=None, rows=None, keys=None):
+    """-> dict(dq, dk, dv, out, lse) float64; out/lse are the oracle's own forward.
+
+    rows=(i0,i1) / keys=(j0,j1) restrict dq to those query rows and dk/dv to those keys (the
+    rest is NaN); the forward is then only computed for the rows that are needed."""
     q, qp = _f32(q)
     k, kp = _f32(k)
     v, vp = _f32(v)
@@ -118,13 +123,15 @@ def bwd(q, k, v, dout, sink, window, block=1, stride=0, scale=None):
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
     assert k.shape == (B, Hkv, N, D) and v.shape == k.shape and dout.shape == q.shape
-    dq = np.zeros((B, Hq, N, D), dtype=np.float64)
-    dk = np.zeros((B, Hkv, N, D), dtype=np.float64)
-    dv = np.zeros((B, Hkv, N, D), dtype=np.float64)
-    out = np.zeros((B, Hq, N, D), dtype=np.float64)
-    lse = np.zeros((B, Hq, N), dtype=np.float64)
-    _load().lgo_bwd(qp, kp, vp, gp, _dptr(dq), _dptr(dk), _dptr(dv), _dptr(out), _dptr(lse),
-                    B, Hq, Hkv, N, D, sink, window, block, stride, _scale(scale, D))
+    dq = np.full((B, Hq, N, D), np.nan, dtype=np.float64)
+    dk = np.full((B, Hkv, N, D), np.nan, dtype=np.float64)
+    dv = np.full((B, Hkv, N, D), np.nan, dtype=np.float64)
+    out = np.full((B, Hq, N, D), np.nan, dtype=np.float64)
+    lse = np.full((B, Hq, N), np.nan, dtype=np.float64)
+    i0, i1 = (0, N) if rows is None else rows
+    j0, j1 = (0, N) if keys is None else keys
+    _load().lgo_bwd_part(qp, kp, vp, gp, _dptr(dq), _dptr(dk), _dptr(dv), _dptr(out), _dptr(lse),
+                         B, Hq, Hkv, N, D, sink, window, block, stride, _scale(scale, D), i0, i1, j0, j1)
     return dict(dq=dq, dk=dk, dv=dv, out=out, lse=lse)
 
 

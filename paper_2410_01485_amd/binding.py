@@ -40,6 +40,9 @@ def lib():
         L.lg_sparse_attn_bwd_workspace_bytes.restype = _sz
         L.lg_sparse_attn_bwd.argtypes = [_vp] * 9 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
         L.lg_sparse_attn_bwd.restype = _i
+        L.lg_debug_bwd_kernel_ms.argtypes = [_vp] * 9 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp,
+                                                                             ctypes.POINTER(_f)]
+        L.lg_debug_bwd_kernel_ms.restype = _i
         L.lg_sparse_attn_decode_workspace_bytes.argtypes = [_i] * 8
         L.lg_sparse_attn_decode_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
@@ -112,6 +115,22 @@ def lg_sparse_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink, win
                                   _stream(q))
     if st != 0:
         raise LgError(st, "lg_sparse_attn_bwd")
+
+
+def lg_debug_bwd_kernel_ms(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink, window, block=1, stride=0,
+                           scale=0.0):
+    """lg_sparse_attn_bwd with per-kernel HIP-event timing: returns [delta_ms, dq_ms, dkdv_ms]."""
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    ms = (_f * 3)()
+    st = lib().lg_debug_bwd_kernel_ms(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                      _ptr(dk), _ptr(dv), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(),
+                                      B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
+                                      _stream(q), ms)
+    if st != 0:
+        raise LgError(st, "lg_debug_bwd_kernel_ms")
+    return [float(x) for x in ms]
 
 
 def decode_workspace_bytes(B, Hq, Hkv, N, D, sink, window, dtype):

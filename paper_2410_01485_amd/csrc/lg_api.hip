@@ -76,12 +76,12 @@ size_t lg_sparse_attn_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
                                 lg_make_mask(N, sink, window, block, stride), dtype);
 }
 
-int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                       const void* dout, void* dq, void* dk, void* dv,
-                       void* workspace, size_t workspace_bytes,
-                       int B, int Hq, int Hkv, int N, int D,
-                       int sink, int window, int block, int stride,
-                       int dtype, float scale, void* hip_stream) {
+static int bwd_impl(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    const void* dout, void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes,
+                    int B, int Hq, int Hkv, int N, int D,
+                    int sink, int window, int block, int stride,
+                    int dtype, float scale, void* hip_stream, float* kernel_ms) {
   if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return LG_ERR_NULL;
   int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
   if (st != LG_OK) return st;
@@ -92,11 +92,44 @@ int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* 
   const LgMask m = lg_make_mask(N, sink, window, block, stride);
   if (!workspace || workspace_bytes < lg_bwd_workspace_bytes(sh, m, dtype)) return LG_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t evs[4];
+  hipEvent_t* ev = nullptr;
+  if (kernel_ms) {
+    for (int x = 0; x < 4; ++x)
+      if (hipEventCreate(&evs[x]) != hipSuccess) return LG_ERR_LAUNCH;
+    ev = evs;
+  }
   hipError_t e = (dtype == LG_F32)
       ? lg_launch_bwd_f32((const float*)q, (const float*)k, (const float*)v, (const float*)out, lse,
-                          (const float*)dout, (float*)dq, (float*)dk, (float*)dv, workspace, sh, m, s)
-      : lg_launch_bwd_bf16(q, k, v, out, lse, dout, dq, dk, dv, workspace, sh, m, s);
+                          (const float*)dout, (float*)dq, (float*)dk, (float*)dv, workspace, sh, m, s, ev)
+      : lg_launch_bwd_bf16(q, k, v, out, lse, dout, dq, dk, dv, workspace, sh, m, s, ev);
+  if (kernel_ms) {
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    for (int x = 0; x < 3 && e == hipSuccess; ++x) e = hipEventElapsedTime(&kernel_ms[x], evs[x], evs[x + 1]);
+    for (int x = 0; x < 4; ++x) hipEventDestroy(evs[x]);
+  }
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes,
+                       int B, int Hq, int Hkv, int N, int D,
+                       int sink, int window, int block, int stride,
+                       int dtype, float scale, void* hip_stream) {
+  return bwd_impl(q, k, v, out, lse, dout, dq, dk, dv, workspace, workspace_bytes, B, Hq, Hkv, N, D, sink,
+                  window, block, stride, dtype, scale, hip_stream, nullptr);
+}
+
+int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes,
+                           int B, int Hq, int Hkv, int N, int D,
+                           int sink, int window, int block, int stride,
+                           int dtype, float scale, void* hip_stream, float* kernel_ms) {
+  if (!kernel_ms) return LG_ERR_NULL;
+  return bwd_impl(q, k, v, out, lse, dout, dq, dk, dv, workspace, workspace_bytes, B, Hq, Hkv, N, D, sink,
+                  window, block, stride, dtype, scale, hip_stream, kernel_ms);
 }
 
 static int check_decode(int B, int Hq, int Hkv, int N, int D, int sink, int window, int block,

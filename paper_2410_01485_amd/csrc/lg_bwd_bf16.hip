@@ -282,10 +282,13 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
 
 hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const void* out,
                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
-                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s) {
+                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
+                              hipEvent_t* ev) {
   float* delta = (float*)ws;
+  if (ev) hipEventRecord(ev[0], s);
   hipError_t e = lg_launch_delta(dout, out, delta, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
   if (e != hipSuccess) return e;
+  if (ev) hipEventRecord(ev[1], s);
   const uint16_t* uq = (const uint16_t*)q;
   const uint16_t* uk = (const uint16_t*)k;
   const uint16_t* uv = (const uint16_t*)v;
@@ -303,6 +306,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
                                                            sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (ev) hipEventRecord(ev[2], s);
   }
   {
     const int nkt = (sh.N + LG_BF16_BTK - 1) / LG_BF16_BTK;
@@ -317,6 +321,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
                                                              (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,
                                                              total, per_xcd);
     e = hipGetLastError();
+    if (ev) hipEventRecord(ev[3], s);
   }
   return e;
 }

@@ -34,12 +34,16 @@ hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void*
 hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, long long rows, int D,
                            int dtype, hipStream_t s);
 size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype);
+// ev: NULL, or 4 events recorded before the Delta pre-pass, between the kernels and after the
+// last one (measurement aid).
 hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, const float* out,
                              const float* lse, const float* dout, float* dq, float* dk, float* dv,
-                             void* ws, const LgShape& sh, const LgMask& m, hipStream_t s);
+                             void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
+                             hipEvent_t* ev);
 hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const void* out,
                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
-                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s);
+                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
+                              hipEvent_t* ev);
 
 // Decode: C = sink + window cache slots per (b, hkv), `valid` of them in use.
 int lg_decode_splits(int B, int Hkv, int valid);

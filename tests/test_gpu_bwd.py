@@ -94,3 +94,32 @@ def test_bwd_deterministic():
 def test_config3_shape_reduced_n_all_heads():
     # config 3's heads, head dim, sink and window at a sequence the oracle finishes: N = 6144
     check_bwd(1, 32, 32, 6144, 128, 64, 4096, dtype=torch.bfloat16, seed=20241004)
+
+
+def test_config3_full_size_sampled():
+    """Training-step configuration as the benchmark launches it: B1, 32 heads, N=131072, D=128, sink 64,
+    window 4096.  The oracle recomputes sampled query rows (dq) and sampled keys (dk, dv) of two heads."""
+    B, H, N, D, sink, window = 1, 32, 131072, 128, 64, 4096
+    q, k, v, g = lg_synth.prefill_inputs(B, H, H, N, D, 20241004, torch.bfloat16, with_dout=True, device=DEV)
+    out = torch.empty_like(q)
+    lse = torch.empty(B, H, N, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window)
+    ws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, sink, window, 1, 0, lg.LG_BF16),
+                     dtype=torch.uint8, device=DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    tol, rel = TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16]
+    for h, rows, keys in ((0, (0, 40), (0, 40)),                      # first rows; sink keys (seen by every row)
+                          (0, (4080, 4120), (4140, 4180)),            # where the window starts to slide
+                          (21, (70001, 70041), (99990, 100030)),      # steady state
+                          (31, (N - 40, N), (N - 40, N))):            # ragged end of the sequence
+        print("head", h, "rows", rows, "keys", keys, flush=True)
+        a = [f32np(x[:, h:h + 1]) for x in (q, k, v, g)]
+        w = O.bwd(*a, sink, window, rows=rows, keys=keys)
+        assert_close(f32np(dq[0, h, rows[0]:rows[1]]), w["dq"][0, 0, rows[0]:rows[1]], tol, rel, "cfg3 dq h%d" % h)
+        assert_close(f32np(dk[0, h, keys[0]:keys[1]]), w["dk"][0, 0, keys[0]:keys[1]], tol, rel, "cfg3 dk h%d" % h)
+        assert_close(f32np(dv[0, h, keys[0]:keys[1]]), w["dv"][0, 0, keys[0]:keys[1]], tol, rel, "cfg3 dv h%d" % h)
+        assert_close(f32np(out[0, h, rows[0]:rows[1]]), w["out"][0, 0, rows[0]:rows[1]], tol, rel, "cfg3 out h%d" % h)

@@ -247,3 +247,14 @@ def test_decode_invariant_under_slot_permutation():
     out3, _ = O.decode(q, kc3, vc3, 5, sink, window)
     want = sdpa(q[:, :, None], kc[:, :, :5], vc[:, :, :5]).numpy()[:, :, 0]
     assert np.abs(out3 - want).max() < 1e-13
+
+
+def test_partial_backward_equals_slices_of_the_full_one():
+    N, D = 120, 8
+    q, k, v, g = inputs(1, 4, 2, N, D, seed=26, with_dout=True)
+    full = O.bwd(q, k, v, g, 6, 20, 2, 9)
+    part = O.bwd(q, k, v, g, 6, 20, 2, 9, rows=(50, 71), keys=(3, 30))
+    assert np.array_equal(part["dq"][:, :, 50:71], full["dq"][:, :, 50:71])
+    assert np.array_equal(part["dk"][:, :, 3:30], full["dk"][:, :, 3:30])
+    assert np.array_equal(part["dv"][:, :, 3:30], full["dv"][:, :, 3:30])
+    assert np.isnan(part["dq"][:, :, :50]).all() and np.isnan(part["dk"][:, :, 30:]).all()
