@@ -205,8 +205,10 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
     for (int u = 0; u < nq; ++u) {
       mark_row();
       const int q0 = u * Tq, q1 = (q0 + Tq - 1 < N - 1) ? q0 + Tq - 1 : N - 1;
-      for (int t = lg_next_ktile(m, q0, q1, Tk, -1); t >= 0; t = lg_next_ktile(m, q0, q1, Tk, t))
-        emit(t, lg_tile_kind(m, q0, q1, t * Tk, t * Tk + Tk - 1));
+      // the per-query-tile schedule the kernels' main loops run
+      const LgQSched qs = lg_qsched_init(m, q0, q1);
+      for (int t = lg_qsched_next(m, qs, -1); t >= 0; t = lg_qsched_next(m, qs, t))
+        emit(t, lg_qsched_full(m, qs, t) ? LG_TILE_FULL : LG_TILE_PARTIAL);
     }
   } else {
     const int nk = (N + Tk - 1) / Tk;

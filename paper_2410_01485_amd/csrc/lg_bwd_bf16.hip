@@ -26,17 +26,20 @@ namespace {
 constexpr float LOG2E = 1.44269504088896340736f;
 
 // ------------------------------------------------------------------------- dq
+// 8 waves x 32 query rows; threads 0..255 stage K (row-major and transposed), threads
+// 256..511 stage V (row-major); tiles double-buffered in LDS.
 template <int D>
-__global__ __launch_bounds__(256, 2) void dq_bf16_kernel(
+__global__ __launch_bounds__(512) void dq_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
     uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m, int nqt, int total, int per_xcd) {
   using T = LgTile<D>;
   constexpr int TQ = LG_BF16_TQ, TK = LG_BF16_TK;
-  static_assert(TQ == 128, "one 32-row query block per wave");
+  static_assert(TQ == 256, "8 waves x 32 query rows");
   constexpr int DC = D / 16, DB = D / 32;
   constexpr int OFF_KT = T::RM_BYTES, OFF_V = T::RM_BYTES + T::T_BYTES;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * T::RM_BYTES + T::T_BYTES];
+  constexpr int STAGE = 2 * T::RM_BYTES + T::T_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
 
   const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (L >= total) return;
@@ -49,7 +52,8 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(
   const int n = lane & 31, g = lane >> 5;
   const int q0 = qt * TQ, q1 = min(q0 + TQ - 1, N - 1);
   const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
   const int i = q0 + wave * 32 + n;
   const int iq = min(i, N - 1);
 
@@ -69,44 +73,53 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-  LgStager<D> kst, vst;
-  kst.init(tid);
-  vst.init(tid);
-  const uint16_t* kh = k + kbase;
-  const uint16_t* vh = v + kbase;
-
-  int t = lg_next_ktile(m, q0, q1, TK, -1);
-  kst.load(kh, t * TK, N);
-  vst.load(vh, t * TK, N);
-  while (t >= 0) {
-    __syncthreads();  // previous tile fully consumed
-    kst.store_rm(smem);
-    kst.store_t(smem + OFF_KT);
-    vst.store_rm(smem + OFF_V);
-    __syncthreads();
-    const int tn = lg_next_ktile(m, q0, q1, TK, t);
-    if (tn >= 0) {
-      kst.load(kh, tn * TK, N);
-      vst.load(vh, tn * TK, N);
+  const bool is_k = tid < 256;
+  LgStager<D> st;
+  st.init(tid & 255, is_k);
+  LgReader<D> rd;
+  rd.init(n, g);
+  const uint16_t* src = is_k ? kh : vh;
+  auto load_tile = [&](int t) { st.load(src + (size_t)t * TK * D, N - t * TK); };
+  auto store_tile = [&](int buf) {
+    unsigned char* s = smem + buf * STAGE;
+    if (is_k) {
+      st.store_rm(s);
+      st.store_t(s + OFF_KT);
+    } else {
+      st.store_rm(s + OFF_V);
     }
+  };
+
+  const LgQSched qs = lg_qsched_init(m, q0, q1);
+  int t = lg_qsched_next(m, qs, -1);
+  load_tile(t);
+  store_tile(0);
+  __syncthreads();
+  int buf = 0;
+  while (t >= 0) {
+    const int tn = lg_qsched_next(m, qs, t);
+    if (tn >= 0) load_tile(tn);
     const int k0 = t * TK;
-    const bool full = lg_tile_kind(m, q0, q1, k0, k0 + TK - 1) == LG_TILE_FULL;
+    const bool full = lg_qsched_full(m, qs, t);
+    const unsigned char* s = smem + buf * STAGE;
+    uint32_t bits = 0xffffffffu;
+    if (!full) bits = lg_live_bits_q(m, i, k0, g);
 
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      f32x16_t s, dp;
+      f32x16_t sc, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+      for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
       for (int dc = 0; dc < DC; ++dc) {
-        s = lg_mfma32(lg_read_rm<D>(smem, kb, n, g, dc), qf[dc], s);
-        dp = lg_mfma32(lg_read_rm<D>(smem + OFF_V, kb, n, g, dc), gf[dc], dp);
+        sc = lg_mfma32(rd.read_rm(s, kb, dc), qf[dc], sc);
+        dp = lg_mfma32(rd.read_rm(s + OFF_V, kb, dc), gf[dc], dp);
       }
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(s[r], sl2, -lse2));
-        if (!full && !lg_live(m, i, k0 + kb * 32 + lg_crow(r, g))) p = 0.f;
+        float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -lse2));
+        if (!full && !(bits & (1u << (kb * 16 + r)))) p = 0.f;
         ds[r] = p * (dp[r] - di);
       }
 #pragma unroll
@@ -114,9 +127,12 @@ __global__ __launch_bounds__(256, 2) void dq_bf16_kernel(
         const bf16x8_t bop = lg_pack_acc(ds + 8 * h);
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-          acc[db] = lg_mfma32(lg_read_t(smem + OFF_KT, db, n, g, 2 * kb + h), bop, acc[db]);
+          acc[db] = lg_mfma32(rd.read_t(s + OFF_KT, db, 2 * kb + h), bop, acc[db]);
       }
     }
+    if (tn >= 0) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
     t = tn;
   }
 
@@ -181,15 +197,17 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
   const int steps = per_head * G;
 
   LgStager<D> qst, gst;
-  qst.init(tid);
-  gst.init(tid);
+  qst.init(tid, true);
+  gst.init(tid, true);
+  LgReader<D> rd;
+  rd.init(n, g);
   float lreg = 0.f;  // threads 0..63 stage lse, 64..127 stage Delta
   auto load_step = [&](int s) {
     const int hq = hk * G + s / per_head;
     const int q0 = (lo + s % per_head) * TQ;
-    const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-    qst.load(q + qbase, q0, N);
-    gst.load(dout + qbase, q0, N);
+    const size_t qbase = ((size_t)(b * Hq + hq) * N + q0) * D;
+    qst.load(q + qbase, N - q0);
+    gst.load(dout + qbase, N - q0);
     if (tid < 2 * TQ) {
       const int row = min(q0 + (tid & (TQ - 1)), N - 1);
       const float* src = tid < TQ ? lse : delta;
@@ -216,6 +234,15 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
     const bool full = lg_tile_kind(m, q0, q1, k0, k0 + TK - 1) == LG_TILE_FULL && q0 + TQ <= N;
     const unsigned char* s = smem + buf * STAGE;
     const float* sL = reinterpret_cast<const float*>(s + OFF_L);
+    uint32_t bits = 0xffffffffu;
+    if (!full) {
+      bits = 0;
+#pragma unroll 1
+      for (int r = 0; r < 32; ++r) {
+        const int i = q0 + (r >> 4) * 32 + lg_crow(r & 15, g);
+        bits |= (uint32_t)(i < N && lg_live(m, i, j)) << r;
+      }
+    }
 
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -224,8 +251,8 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
       for (int r = 0; r < 16; ++r) sc[r] = dp[r] = 0.f;
 #pragma unroll
       for (int dc = 0; dc < DC; ++dc) {
-        sc = lg_mfma32(lg_read_rm<D>(s, qb, n, g, dc), kf[dc], sc);
-        dp = lg_mfma32(lg_read_rm<D>(s + OFF_G, qb, n, g, dc), vf[dc], dp);
+        sc = lg_mfma32(rd.read_rm(s, qb, dc), kf[dc], sc);
+        dp = lg_mfma32(rd.read_rm(s + OFF_G, qb, dc), vf[dc], dp);
       }
       float p[16], ds[16];
 #pragma unroll
@@ -238,10 +265,7 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
         for (int t = 0; t < 4; ++t) {
           const int r = 4 * r4 + t;
           float pv = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -lv[t]));
-          if (!full) {
-            const int i = q0 + qb * 32 + lg_crow(r, g);
-            if (i >= N || !lg_live(m, i, j)) pv = 0.f;
-          }
+          if (!full && !(bits & (1u << (qb * 16 + r)))) pv = 0.f;
           p[r] = pv;
           ds[r] = pv * (dp[r] - dv4[t]);
         }
@@ -252,8 +276,8 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
         const bf16x8_t db_ = lg_pack_acc(ds + 8 * h);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          av[db] = lg_mfma32(lg_read_t(s + OFF_GT, db, n, g, 2 * qb + h), pb, av[db]);
-          ak[db] = lg_mfma32(lg_read_t(s + OFF_QT, db, n, g, 2 * qb + h), db_, ak[db]);
+          av[db] = lg_mfma32(rd.read_t(s + OFF_GT, db, 2 * qb + h), pb, av[db]);
+          ak[db] = lg_mfma32(rd.read_t(s + OFF_QT, db, 2 * qb + h), db_, ak[db]);
         }
       }
     }
@@ -299,10 +323,10 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
     const int total = (int)tl, per_xcd = (total + 7) / 8;
     if (sh.D == 64)
-      dq_bf16_kernel<64><<<dim3(per_xcd * 8), 256, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
+      dq_bf16_kernel<64><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
                                                           sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     else
-      dq_bf16_kernel<128><<<dim3(per_xcd * 8), 256, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
+      dq_bf16_kernel<128><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
                                                            sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     e = hipGetLastError();
     if (e != hipSuccess) return e;

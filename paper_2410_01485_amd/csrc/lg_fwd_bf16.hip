@@ -1,41 +1,44 @@
 // lg_fwd_bf16.hip — bf16 prefill forward on the gfx950 matrix cores (paper Section
 // 3.2: fused online-softmax attention that never loads key tiles whose mask is zero).
 //
-// Workgroup = 4 wavefronts = TQ query rows of one (b, hq); wave w owns 32*QB rows.
-// Per live key tile (64 keys, taken from the closed-form scheduler in lg_mask.h):
-//   S^T = K Q^T     (keys x queries): A = K tile from LDS, B = Q kept in registers
+// Workgroup = 8 wavefronts = 256 query rows of one (b, hq); wave w owns 32 rows.
+// Two waves share each SIMD, so one wave's softmax (vector ALU) overlaps the other's
+// matrix work.  Per live key tile (64 keys, from the closed-form scheduler in lg_mask.h):
+//   S^T = K Q^T     (keys x queries): A = K rows from LDS, B = Q kept in registers
 //   online softmax  on S^T: a lane holds 32 keys of ONE query, so row max / row sum
 //                   are in-lane reductions plus one exchange with lane^32
-//   O^T += V^T P^T  (dims x queries): A = V^T from LDS, B = P^T straight from the
-//                   S^T accumulator registers (no shuffle: the key order of the
-//                   contraction slots is chosen to match the accumulator layout and
-//                   V^T is stored in LDS in that same order)
-// K and V tiles are double-buffered in LDS: the global loads of tile t+1 are issued
-// before the matrix work of tile t and written to the other buffer afterwards.
+//   O^T += V^T P^T  (dims x queries): A = V read from LDS through the transposing
+//                   LDS load, B = P^T straight from the S^T accumulator registers
+// K and V tiles travel global -> LDS directly (no registers) into a 4-stage ring;
+// tiles t+1..t+3 are in flight while tile t is computed, one barrier per tile.
 // Masking is applied only on PARTIAL tiles.
 #include "lg_kernels.h"
 #include "lg_mfma.h"
-#include "lg_stage.h"
+#include "lg_swz.h"
 
 namespace {
 
-constexpr int TK = LG_BF16_TK;           // 64 keys per step (= LgTile::ROWS)
-constexpr int QB = LG_BF16_TQ / 128;     // 32-row query blocks per wave
-constexpr int TQ = LG_BF16_TQ;
+constexpr int TK = LG_BF16_TK;  // 64 keys per step
+constexpr int TQ = LG_BF16_TQ;  // 256 query rows per workgroup
+constexpr int NT = TQ * 2;      // threads: one wave per 32 rows
+constexpr int STAGES = 4;
+static_assert(TQ == 256 && TK == 64, "8 waves x 32 rows, 64-key tiles");
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const uint16_t* __restrict__ q,
-                                                       const uint16_t* __restrict__ k,
-                                                       const uint16_t* __restrict__ v,
-                                                       uint16_t* __restrict__ out,
-                                                       float* __restrict__ lse, int Hq, int Hkv,
-                                                       float scale_log2e, LgMask m, int nqt,
-                                                       int total, int per_xcd) {
-  using T = LgTile<D>;
-  constexpr int DC = D / 16;  // 16-wide contraction chunks of the head dim
-  constexpr int DB = D / 32;  // 32-row blocks of O^T
-  constexpr int STAGE = T::RM_BYTES + T::T_BYTES;  // K row-major + V transposed
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+__global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict__ q,
+                                                      const uint16_t* __restrict__ k,
+                                                      const uint16_t* __restrict__ v,
+                                                      uint16_t* __restrict__ out,
+                                                      float* __restrict__ lse, int Hq, int Hkv,
+                                                      float scale_log2e, LgMask m, int nqt,
+                                                      int total, int per_xcd) {
+  using T = LgSwzTile<D>;
+  using Dma = LgDma<D, NT>;
+  constexpr int DC = D / 16;            // 16-wide contraction chunks of the head dim
+  constexpr int DB = D / 32;            // 32-row blocks of O^T
+  constexpr int STAGE = 2 * T::BYTES;   // K tile + V tile
+  constexpr int LPT = 2 * Dma::CH;      // direct loads per thread per tile
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[STAGES * STAGE];
 
   // XCD-aware order: workgroup ids are dealt round-robin to the 8 XCDs, so give
   // each XCD one contiguous run of the logical (head, query tile) sequence; its L2
@@ -53,164 +56,166 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const uint16_t* __rest
   const int q0 = qt * TQ;
   const int q1 = min(q0 + TQ - 1, N - 1);
   const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const int i = q0 + wave * 32 + n;  // this lane's query row
 
   // Q fragments (B operand): lane (n, g) holds dims 16*dc + 8g .. +7 of its row.
-  bf16x8_t qf[QB][DC];
-  int qrow[QB];
+  bf16x8_t qf[DC];
+  {
+    const uint16_t* qr = q + qbase + (size_t)min(i, N - 1) * D + g * 8;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    qrow[qb] = q0 + (wave * QB + qb) * 32 + n;
-    const int rq = min(qrow[qb], N - 1);
+    for (int dc = 0; dc < DC; ++dc) qf[dc] = lg_as_bf16x8(*reinterpret_cast<const uint4*>(qr + dc * 16));
+    // Touch the fragments here so that the compiler's own wait for these loads sits before
+    // the tile ring starts: a wait placed inside the loop would also drain the direct loads
+    // that are meant to stay in flight.
 #pragma unroll
-    for (int dc = 0; dc < DC; ++dc)
-      qf[qb][dc] = lg_as_bf16x8(*reinterpret_cast<const uint4*>(q + qbase + (size_t)rq * D + dc * 16 + g * 8));
+    for (int dc = 0; dc < DC; ++dc) asm volatile("" ::"v"(qf[dc]));
   }
 
-  f32x16_t oacc[QB][DB];
-  float mrow[QB], lrow[QB];
+  f32x16_t oacc[DB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    mrow[qb] = -INFINITY;
-    lrow[qb] = 0.f;
+  for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float mrow = -INFINITY, mref = -INFINITY, lrow = 0.f;
+
+  Dma dma;
+  dma.init(tid);
+  LgSwzReader<D> rd;
+  rd.init(n, g);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)LG_LDS_PTR(unsigned char, smem);
+  const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  auto issue = [&](int t, int stage) {
+    const size_t off = (size_t)t * TK * D;
+    dma.issue(kh + off, N - t * TK, lds0 + stage * STAGE);
+    dma.issue(vh + off, N - t * TK, lds0 + stage * STAGE + T::BYTES);
+  };
+
+  // ring: tiles are issued up to 3 ahead of the one being computed
+  const LgQSched qs = lg_qsched_init(m, q0, q1);
+  int t = lg_qsched_next(m, qs, -1);  // tile to compute next
+  int t_issue = t;                           // tile to issue next
+  int ahead = 0;                             // tiles issued and not yet computed
+  for (; ahead < STAGES - 1 && t_issue >= 0; ++ahead) {
+    issue(t_issue, ahead);
+    t_issue = lg_qsched_next(m, qs, t_issue);
   }
 
-  // global -> register -> LDS staging of one K/V tile
-  LgStager<D> kst, vst;
-  kst.init(tid);
-  vst.init(tid);
-  const uint16_t* kh = k + kbase;
-  const uint16_t* vh = v + kbase;
-  auto load_tile = [&](int t) {
-    kst.load(kh, t * TK, N);
-    vst.load(vh, t * TK, N);
-  };
-  auto store_tile = [&](int buf) {
-    kst.store_rm(smem + buf * STAGE);
-    vst.store_t(smem + buf * STAGE + T::RM_BYTES);
-  };
-
-  int t = lg_next_ktile(m, q0, q1, TK, -1);
-  load_tile(t);
-  store_tile(0);
-  __syncthreads();
-  int buf = 0;
-
+  int stage = 0;  // ring position of tile t
   while (t >= 0) {
-    const int tn = lg_next_ktile(m, q0, q1, TK, t);
-    if (tn >= 0) load_tile(tn);
+    // this wave's loads of tile t have landed once at most (ahead-1) newer tiles are pending
+    if (ahead >= 3) LG_WAIT_VMCNT(2 * LPT);
+    else if (ahead == 2) LG_WAIT_VMCNT(LPT);
+    else LG_WAIT_VMCNT(0);
+    __syncthreads();  // everyone's loads of tile t landed; everyone is done with tile t-1
+    if (t_issue >= 0) {
+      issue(t_issue, (stage + STAGES - 1) % STAGES);  // into the stage tile t-1 just left
+      t_issue = lg_qsched_next(m, qs, t_issue);
+      ++ahead;
+    }
 
     const int k0 = t * TK;
-    const bool full = lg_tile_kind(m, q0, q1, k0, k0 + TK - 1) == LG_TILE_FULL;
-    const unsigned char* sk = smem + buf * STAGE;
-    const unsigned char* sv = sk + T::RM_BYTES;
+    const bool full = lg_qsched_full(m, qs, t);
+    const int sk = stage * STAGE;   // byte offsets of the K and V tiles inside smem
+    const int sv = sk + T::BYTES;
 
     // ---- S^T = K Q^T ----
-    f32x16_t sacc[2][QB];
+    f32x16_t sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+    for (int dc = 0; dc < DC; ++dc)
 #pragma unroll
-    for (int dc = 0; dc < DC; ++dc) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8_t a = lg_read_rm<D>(sk, kb, n, g, dc);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = lg_mfma32(a, qf[qb][dc], sacc[kb][qb]);
-      }
-    }
+      for (int kb = 0; kb < 2; ++kb) sacc[kb] = lg_mfma32(rd.read_rows(smem, sk, kb, dc), qf[dc], sacc[kb]);
 
     // ---- online softmax (log2 domain) ----
-    bf16x8_t pf[QB][4];  // P^T as bf16, B operand of the second product, per 16-key chunk
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      if (!full) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = k0 + kb * 32 + lg_crow(r, g);
-            if (!lg_live(m, qrow[qb], j)) sacc[kb][qb][r] = -INFINITY;
-          }
+    if (!full) {
+      uint32_t bits = 0;
+#pragma unroll 1
+      for (int r = 0; r < 32; ++r) {
+        const int j = k0 + (r >> 4) * 32 + lg_crow(r & 15, g);
+        bits |= (uint32_t)lg_live(m, i, j) << r;
       }
-      float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-      mx = fmaxf(mx, lg_other_half(mx));
-      const float mnew = fmaxf(mrow[qb], mx);
-      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = __builtin_amdgcn_exp2f((mrow[qb] - msafe) * scale_log2e);
-      const float moff = msafe * scale_log2e;
-      mrow[qb] = mnew;
-      float psum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][r], scale_log2e, -moff));
-          psum += p[r];
-        }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) pf[qb][2 * kb + h] = lg_pack_acc(p + 8 * h);
-      }
-      lrow[qb] = lrow[qb] * alpha + psum;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-      }
+        for (int r = 0; r < 16; ++r)
+          if (!(bits & (1u << (kb * 16 + r)))) sacc[kb][r] = -INFINITY;
     }
-
-    // ---- O^T += V^T P^T ----
+    float mx = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8_t a = lg_read_t(sv, db, n, g, c);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          oacc[qb][db] = lg_mfma32(a, pf[qb][c], oacc[qb][db]);
-      }
-    }
-
-    if (tn >= 0) store_tile(buf ^ 1);
-    __syncthreads();
-    buf ^= 1;
-    t = tn;
-  }
-
-  // ---- epilogue: normalise, write O (bf16) and LSE (natural log) ----
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l = lrow[qb] + lg_other_half(lrow[qb]);
-    const float inv = 1.f / l;
-    const int i = qrow[qb];
-    if (i < N) {
+      for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(sacc[kb][r], sacc[kb][r + 1]), mx);
+    mx = fmaxf(mx, lg_other_half(mx));
+    // Lazy rescaling: the exponent is taken relative to a reference maximum mref that only
+    // moves when the running maximum has grown by more than 2^8 (in the log2 domain), so
+    // P stays below 2^8 (fine for bf16 / float32 accumulation) and the accumulator rescale is
+    // skipped on almost every tile.  lse = mref*c + log2(l) holds for any reference.
+    const float mnew = fmaxf(mrow, mx);
+    mrow = mnew;
+    const bool grow = (mnew - mref) * scale_log2e > 8.0f;  // first live tile: mref = -inf -> true
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      asm volatile("; rescale accumulators" ::: "memory");  // keep this a real branch
+      const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * scale_log2e);
+      mref = mnew;
+      lrow *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          uint2 w;
-          w.x = lg_pack_bf16(oacc[qb][db][4 * r4 + 0] * inv, oacc[qb][db][4 * r4 + 1] * inv);
-          w.y = lg_pack_bf16(oacc[qb][db][4 * r4 + 2] * inv, oacc[qb][db][4 * r4 + 3] * inv);
-          const int d = db * 32 + 8 * r4 + 4 * g;
-          *reinterpret_cast<uint2*>(out + qbase + (size_t)i * D + d) = w;
-        }
-      if (lse != nullptr && g == 0)
-        lse[(size_t)(b * Hq + hq) * N + i] =
-            (mrow[qb] * scale_log2e + log2f(l)) * 0.69314718055994530942f;
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
+    const float moff = (mref == -INFINITY) ? 0.f : mref * scale_log2e;
+    float psum = 0.f;
+    bf16x8_t pf[4];  // P^T as bf16, B operand of the second product, per 16-key group
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint32_t w[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * h + 2 * x], scale_log2e, -moff));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][8 * h + 2 * x + 1], scale_log2e, -moff));
+          w[x] = lg_pack_bf16(p0, p1);
+          // row sum of the ROUNDED probabilities: the same values the second product uses
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w[x]), ones, psum, false);
+        }
+        pf[2 * kb + h] = lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+      }
+    lrow += psum;
+
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) oacc[db] = lg_mfma32(rd.read_cols(smem, sv, db, c), pf[c], oacc[db]);
+
+    --ahead;
+    t = lg_qsched_next(m, qs, t);
+    stage = (stage + 1) % STAGES;
+  }
+
+  // ---- epilogue: normalise, write O (bf16) and LSE (natural log) ----
+  const float l = lrow + lg_other_half(lrow);
+  const float inv = 1.f / l;
+  if (i < N) {
+    uint16_t* orow = out + qbase + (size_t)i * D + 4 * g;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        uint2 w;
+        w.x = lg_pack_bf16(oacc[db][4 * r4 + 0] * inv, oacc[db][4 * r4 + 1] * inv);
+        w.y = lg_pack_bf16(oacc[db][4 * r4 + 2] * inv, oacc[db][4 * r4 + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + db * 32 + 8 * r4) = w;
+      }
+    if (lse != nullptr && g == 0)
+      lse[(size_t)(b * Hq + hq) * N + i] = (mref * scale_log2e + log2f(l)) * 0.69314718055994530942f;
   }
 }
 
@@ -226,10 +231,10 @@ hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void*
   const float sl2 = sh.scale * 1.44269504088896340736f;
   const dim3 grid(per_xcd * 8);
   if (sh.D == 64)
-    fwd_bf16_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
-                                             (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
+    fwd_bf16_kernel<64><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
+                                            (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
   else
-    fwd_bf16_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
-                                              (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
+    fwd_bf16_kernel<128><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
+                                             (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
   return hipGetLastError();
 }

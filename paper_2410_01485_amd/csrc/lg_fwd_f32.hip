@@ -43,9 +43,10 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
   }
   float mrow = -INFINITY, lrow = 0.f;
 
-  for (int t = lg_next_ktile(m, q0, q1, TK, -1); t >= 0; t = lg_next_ktile(m, q0, q1, TK, t)) {
+  const LgQSched qs = lg_qsched_init(m, q0, q1);
+  for (int t = lg_qsched_next(m, qs, -1); t >= 0; t = lg_qsched_next(m, qs, t)) {
     const int k0 = t * TK;
-    const bool full = lg_tile_kind(m, q0, q1, k0, k0 + TK - 1) == LG_TILE_FULL;
+    const bool full = lg_qsched_full(m, qs, t);
     __syncthreads();  // previous tile fully consumed
     for (int e = tid * 4; e < TK * D; e += 256 * 4) {
       const int row = e / D, col = e % D;

@@ -9,6 +9,10 @@
 // lg_next_ktile walks the live key tiles of a query tile in increasing order, and
 // lg_qtile_range gives the (contiguous) live query tiles of a key tile.  The host
 // entry point lg_debug_tile_map materialises the same lists as CSR for checking.
+//
+// Divisions by the block size and remainders by the stride run once per tile inside
+// the kernels' main loops, so power-of-two values (the usual case: 64-token blocks,
+// strides 8 or 64) take a shift / mask path; other values fall back to division.
 #ifndef LG_MASK_H_
 #define LG_MASK_H_
 
@@ -27,7 +31,15 @@ struct LgMask {
   int stride;  // in blocks; 0 = no strided columns
   int sb;      // sink / b
   int wb;      // window / b
+  int bshift;  // log2(b) when b is a power of two, else -1
+  int smask;   // stride - 1 when stride is a power of two, else -1
 };
+
+LG_HD int lg_log2_exact(int x) {
+  for (int s = 0; s < 31; ++s)
+    if ((1 << s) == x) return s;
+  return -1;
+}
 
 LG_HD LgMask lg_make_mask(int N, int sink, int window, int block, int stride) {
   LgMask m;
@@ -41,26 +53,31 @@ LG_HD LgMask lg_make_mask(int N, int sink, int window, int block, int stride) {
   m.sink = m.sb * m.b;
   m.window = m.wb * m.b;
   m.stride = (stride > 0 && stride - 1 < nb) ? stride : 0;
+  m.bshift = lg_log2_exact(m.b);
+  m.smask = (m.stride > 0 && lg_log2_exact(m.stride) >= 0) ? m.stride - 1 : -1;
   return m;
+}
+
+// x / b for x >= 0
+LG_HD int lg_div_b(const LgMask& m, int x) { return m.bshift >= 0 ? (x >> m.bshift) : x / m.b; }
+
+// Is block column kb one of the strided columns (kb % stride == stride - 1)?  stride > 0.
+LG_HD bool lg_strided(const LgMask& m, int kb) {
+  return m.smask >= 0 ? ((kb & m.smask) == m.smask) : (kb % m.stride == m.stride - 1);
+}
+
+// First strided block index >= kb (stride > 0).
+LG_HD int lg_next_strided_block(const LgMask& m, int kb) {
+  return m.smask >= 0 ? (kb | m.smask) : kb + (m.stride - 1 - kb % m.stride);
 }
 
 // live(i, j): may query i attend to key j?
 LG_HD bool lg_live(const LgMask& m, int i, int j) {
   if (j > i) return false;
   if (m.b == 1 && m.stride == 0) return j < m.sink || i - j < m.window;
-  const int qb = i / m.b, kb = j / m.b;
+  const int qb = lg_div_b(m, i), kb = lg_div_b(m, j);
   if (kb < m.sb || qb - kb < m.wb) return true;
-  return m.stride > 0 && kb % m.stride == m.stride - 1;
-}
-
-// Is block column kb kept for every later query (sink or strided column)?
-LG_HD bool lg_block_always_on(const LgMask& m, int kb) {
-  return kb < m.sb || (m.stride > 0 && kb % m.stride == m.stride - 1);
-}
-
-// First strided block index >= kb (stride > 0).
-LG_HD int lg_next_strided_block(const LgMask& m, int kb) {
-  return kb + (m.stride - 1 - kb % m.stride);
+  return m.stride > 0 && lg_strided(m, kb);
 }
 
 enum { LG_TILE_DEAD = 0, LG_TILE_PARTIAL = 1, LG_TILE_FULL = 2 };
@@ -74,9 +91,9 @@ LG_HD int lg_tile_kind(const LgMask& m, int q0, int q1, int k0, int k1) {
   bool live = k0 < m.sink;
   if (!live) {
     const int istar = q0 > je ? q0 : je;  // earliest row that sees key je
-    live = istar / m.b - je / m.b < m.wb;
+    live = lg_div_b(m, istar) - lg_div_b(m, je) < m.wb;
   }
-  if (!live && m.stride > 0) live = lg_next_strided_block(m, k0 / m.b) <= je / m.b;
+  if (!live && m.stride > 0) live = lg_next_strided_block(m, lg_div_b(m, k0)) <= lg_div_b(m, je);
   if (!live) return LG_TILE_DEAD;
   if (k1 > q0) return LG_TILE_PARTIAL;  // crosses the diagonal (or runs past N-1)
   if (m.stride == 1) return LG_TILE_FULL;
@@ -84,34 +101,90 @@ LG_HD int lg_tile_kind(const LgMask& m, int q0, int q1, int k0, int k1) {
   // the window of the last row
   int j = k0;
   for (int it = 0; it < 4 && j <= k1; ++it) {
-    const int kb = j / m.b;
+    const int kb = lg_div_b(m, j);
     if (kb < m.sb) j = m.sink;
-    else if (m.stride > 0 && kb % m.stride == m.stride - 1) j = (kb + 1) * m.b;
+    else if (m.stride > 0 && lg_strided(m, kb)) j = (kb + 1) * m.b;
     else break;
   }
   if (j > k1) return LG_TILE_FULL;
-  return (q1 / m.b - j / m.b < m.wb) ? LG_TILE_FULL : LG_TILE_PARTIAL;
+  return (lg_div_b(m, q1) - lg_div_b(m, j) < m.wb) ? LG_TILE_FULL : LG_TILE_PARTIAL;
 }
 
 // Next live key tile (tile = keys [t*Tk, t*Tk+Tk-1]) after tile `prev` for the query
 // rows [q0, q1]; pass prev = -1 to get the first.  Returns -1 when there is none.
+// Tk must be a power of two.
 LG_HD int lg_next_ktile(const LgMask& m, int q0, int q1, int Tk, int prev) {
   const int t0 = prev + 1;
   const int j0 = t0 * Tk;
   if (j0 > q1) return -1;
   if (j0 < m.sink) return t0;
   // window: live keys of the row range are [jw, q1]
-  int jw = (q0 / m.b - m.wb + 1) * m.b;
+  int jw = (lg_div_b(m, q0) - m.wb + 1) * m.b;
   if (jw < 0) jw = 0;
-  int t = jw / Tk;
+  int t = (int)((unsigned)jw / (unsigned)Tk);
   if (t < t0) t = t0;
   if (m.stride > 0) {
-    const int kb0 = j0 / m.b;
+    const int kb0 = lg_div_b(m, j0);
     const int f = lg_next_strided_block(m, kb0);
-    const int ts = (f == kb0) ? t0 : (int)(((long long)f * m.b) / Tk);
+    const int ts = (f == kb0) ? t0 : (int)(((unsigned long long)f * (unsigned)m.b) / (unsigned)Tk);
     if (ts < t) t = ts;
   }
   return ((long long)t * Tk <= q1) ? t : -1;
+}
+
+// ---------------------------------------------------------------------------------
+// Per-query-tile schedule for the kernels' main loops: the same live key tiles and the
+// same FULL / PARTIAL classes as lg_next_ktile / lg_tile_kind, but with everything that
+// depends only on the query tile computed once, so that one step costs a handful of
+// scalar operations.  Key tiles are Tk = 64 keys.
+struct LgQSched {
+  int tmax;   // last causal key tile: q1 / 64
+  int tS;     // key tiles [0, tS) hold sink keys
+  int tW;     // first key tile that reaches into the window of some row
+  int jfull;  // keys >= jfull are inside the window of every row of the query tile
+  int q0;
+};
+
+LG_HD LgQSched lg_qsched_init(const LgMask& m, int q0, int q1) {
+  LgQSched s;
+  s.q0 = q0;
+  s.tmax = q1 >> 6;
+  s.tS = (m.sink + 63) >> 6;
+  int jw = (lg_div_b(m, q0) - m.wb + 1) * m.b;
+  s.tW = jw > 0 ? (jw >> 6) : 0;
+  const int jf = (lg_div_b(m, q1) - m.wb + 1) * m.b;
+  s.jfull = jf > 0 ? jf : 0;
+  return s;
+}
+
+// Next live key tile after `prev` (-1 for the first), or -1.
+LG_HD int lg_qsched_next(const LgMask& m, const LgQSched& s, int prev) {
+  int t = prev + 1;
+  if (t >= s.tS && t < s.tW) {  // in the gap between the sink tiles and the window tiles
+    int ts = s.tW;
+    if (m.stride > 0) {
+      const int kb0 = lg_div_b(m, t << 6);
+      const int f = lg_next_strided_block(m, kb0);
+      const int tf = (f == kb0) ? t : (int)(((unsigned long long)f * (unsigned)m.b) >> 6);
+      ts = tf < ts ? tf : ts;
+    }
+    t = ts;
+  }
+  return t <= s.tmax ? t : -1;
+}
+
+// Is live key tile t FULL (every pair live, nothing to mask)?
+LG_HD bool lg_qsched_full(const LgMask& m, const LgQSched& s, int t) {
+  const int k0 = t << 6, k1 = k0 + 63;
+  if (k1 > s.q0) return false;                       // crosses the diagonal or the end
+  if (k0 >= s.jfull || k1 < m.sink || s.jfull <= m.sink) return true;
+  if (m.stride == 0) return false;
+  if (m.stride == 1) return true;
+  // the keys below jfull that are not sink keys must all lie in one strided block
+  const int lo = k0 > m.sink ? k0 : m.sink;
+  const int hi = k1 < s.jfull - 1 ? k1 : s.jfull - 1;
+  const int kb = lg_div_b(m, lo);
+  return kb == lg_div_b(m, hi) && lg_strided(m, kb);
 }
 
 // Live query tiles (tile = rows [u*Tq, u*Tq+Tq-1]) of the keys [k0, k1] (k1 <= N-1):
@@ -119,10 +192,10 @@ LG_HD int lg_next_ktile(const LgMask& m, int q0, int q1, int Tk, int prev) {
 LG_HD void lg_qtile_range(const LgMask& m, int k0, int k1, int Tq, int* lo, int* hi) {
   *lo = k0 / Tq;
   bool always = k0 < m.sink;
-  if (!always && m.stride > 0) always = lg_next_strided_block(m, k0 / m.b) <= k1 / m.b;
+  if (!always && m.stride > 0) always = lg_next_strided_block(m, lg_div_b(m, k0)) <= lg_div_b(m, k1);
   long long last = m.N - 1;
   if (!always) {
-    const long long w = ((long long)(k1 / m.b) + m.wb) * m.b - 1;  // last row whose window holds k1
+    const long long w = ((long long)lg_div_b(m, k1) + m.wb) * m.b - 1;  // last row whose window holds k1
     if (w < last) last = w;
   }
   *hi = (int)(last / Tq);
