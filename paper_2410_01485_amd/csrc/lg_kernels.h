@@ -16,7 +16,7 @@ enum {
   LG_F32_TQ = 64, LG_F32_TK = 64,        // float32 kernels, forward / dq order
   LG_F32_BTQ = 64, LG_F32_BTK = 64,      // float32 dk/dv kernel (key-tile major)
   LG_BF16_TQ = 256, LG_BF16_TK = 64,     // bf16 MFMA forward and dq kernels
-  LG_BF16_BTQ = 64, LG_BF16_BTK = 128    // bf16 MFMA dk/dv kernel (key-tile major)
+  LG_BF16_BTQ = 64, LG_BF16_BTK = 256    // bf16 MFMA dk/dv kernel (key-tile major)
 };
 
 struct LgShape {

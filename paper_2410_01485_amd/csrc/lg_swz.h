@@ -39,8 +39,9 @@ struct LgSwzTile {
   }
 };
 
-// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left unconstrained), n < 16
-#define LG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left unconstrained), n < 64: the count sits in
+// bits [3:0] and [15:14] of the immediate
+#define LG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 // Direct global->LDS copy of one tile by NT threads.
 template <int D, int NT>
@@ -49,15 +50,14 @@ struct LgDma {
   static constexpr int CH = T::ROWS * T::CPR / NT;  // 16-byte chunks per thread
   static_assert(CH >= 1, "tile smaller than the workgroup");
   uint32_t voff[CH];   // global byte offset of this lane's chunk inside the tile
-  int row[CH];         // its tile row (for clamping on a ragged tile)
   uint32_t wave_off;   // LDS byte offset of this wave's first chunk inside the tile
   __device__ __forceinline__ void init(int tid) {
 #pragma unroll
     for (int x = 0; x < CH; ++x) {
       const int p = x * NT + tid;
-      row[x] = p / T::CPR;
-      const int chunk = (p % T::CPR) ^ T::pi(row[x]);
-      voff[x] = row[x] * T::ROW_BYTES + chunk * 16;
+      const int row = p / T::CPR;
+      const int chunk = (p % T::CPR) ^ T::pi(row);
+      voff[x] = row * T::ROW_BYTES + chunk * 16;
     }
     wave_off = (tid & ~63) * 16;
   }
@@ -68,9 +68,10 @@ struct LgDma {
 #pragma unroll
     for (int x = 0; x < CH; ++x) {
       uint32_t off = voff[x];
-      if (rows_left < T::ROWS) {
-        const int r = min(row[x], rows_left - 1);
-        off = off - row[x] * T::ROW_BYTES + r * T::ROW_BYTES;
+      if (rows_left < T::ROWS) {  // ragged tile: rows past the end repeat the last valid row
+        const int row = (int)(off / T::ROW_BYTES);
+        const int r = min(row, rows_left - 1);
+        off = off - row * T::ROW_BYTES + r * T::ROW_BYTES;
       }
       const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds + wave_off + x * NT * 16);
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(off), "s"(src)
@@ -78,6 +79,13 @@ struct LgDma {
     }
   }
 };
+
+// Direct global->LDS copy of 64 consecutive floats by one wave: lane l fetches src[l]
+// (src is this lane's own address) and the wave's 256 bytes land contiguously at `lds`.
+__device__ __forceinline__ void lg_dma_f32x64(const float* lane_src, uint32_t lds) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(m0), "v"(lane_src) : "memory");
+}
 
 // Per-lane read offsets into a swizzled tile (lane = 32g + n).  Only two lane-dependent
 // bases are kept in registers; the per-chunk addresses differ from them by XORs with small
