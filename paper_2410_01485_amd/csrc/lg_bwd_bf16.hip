@@ -185,9 +185,24 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, lse*log2e | Delta (2 x 64 floats)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[VRES + 2 * STAGE];
 
-  const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (L >= total) return;
-  const int bh = L / nkt, kt = L % nkt;  // key tile 0 (sink: longest query range) first
+  // Launch order.  Key tile 0 of every (b, kv head) holds the sink keys, which every later
+  // query tile attends to: its workgroup runs ~N/64 steps instead of ~(window+256)/64.  Those
+  // nbh workgroups take the first block ids (dealt round-robin over the XCDs, so they start
+  // at once and spread evenly); the remaining (head, key tile) items follow in XCD-contiguous
+  // chunks so that neighbouring key tiles share their Q / dO rows in one XCD's L2.
+  // per_xcd counts the chunked items per XCD; total = nbh * nkt items overall.
+  const int nbh = total / nkt;
+  int bh, kt;
+  if ((int)blockIdx.x < nbh) {
+    bh = blockIdx.x;
+    kt = 0;
+  } else {
+    const int idx = blockIdx.x - nbh;
+    const int L = (idx % 8) * per_xcd + idx / 8;
+    if (nkt == 1 || L >= total - nbh) return;
+    bh = L / (nkt - 1);
+    kt = 1 + L % (nkt - 1);
+  }
   const int b = bh / Hkv, hk = bh % Hkv;
   const int G = Hq / Hkv;
   const int N = m.N;
@@ -229,26 +244,37 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   }
   const int voff = (wave >> 1) * T::BYTES + (wave & 1) * HALF;  // this wave's 32 V rows
 
-  auto issue_step = [&](int s, int buf) {
-    const int hq = hk * G + s / per_head;
-    const int q0 = (lo + s % per_head) * TQ;
-    const size_t qb_ = ((size_t)(b * Hq + hq) * N + q0) * D;
+  // (head, query tile) of a step advance incrementally: no divisions in the loop
+  auto issue_step = [&](int hq, int u, int buf) {
+    const int q0 = u * TQ;
+    const size_t row0 = (size_t)(b * Hq + hq) * N;
     const uint32_t st = lds0 + VRES + buf * STAGE;
-    dma.issue(q + qb_, N - q0, st);
-    dma.issue(dout + qb_, N - q0, st + OFF_G);
+    // the small per-row loads go first: anything the compiler makes them wait for must not
+    // include the tile loads issued below
     if (wave < 2) {  // wave 0: lse rows, wave 1: Delta rows (64 floats each)
-      const float* src = (wave == 0 ? lse : delta) + (size_t)(b * Hq + hq) * N + min(q0 + lane, N - 1);
+      const float* src = (wave == 0 ? lse : delta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
+    dma.issue(q + (row0 + q0) * D, N - q0, st);
+    dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
   };
 
-  issue_step(0, 0);
+  int hq_i = hk * G, u_i = lo;   // step being issued
+  int u_c = lo;                  // query tile of the step being computed
+  issue_step(hq_i, u_i, 0);
   for (int st = 0; st < steps; ++st) {
     const int buf = st & 1;
     LG_WAIT_VMCNT(0);
     __syncthreads();  // step st landed for everyone; everyone is done with step st-1
-    if (st + 1 < steps) issue_step(st + 1, buf ^ 1);
-    const int q0 = (lo + st % per_head) * TQ;
+    if (st + 1 < steps) {
+      if (++u_i > hi) {
+        u_i = lo;
+        ++hq_i;
+      }
+      issue_step(hq_i, u_i, buf ^ 1);
+    }
+    const int q0 = u_c * TQ;
+    u_c = (u_c == hi) ? lo : u_c + 1;
     const int q1 = min(q0 + TQ - 1, N - 1);
     const bool full = lg_tile_kind(m, q0, q1, k0 + wave * 32, k0 + wave * 32 + 31) == LG_TILE_FULL && q0 + TQ <= N;
     const int sq = VRES + buf * STAGE, sg = sq + OFF_G;
@@ -371,13 +397,15 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
   {
     const int nkt = (sh.N + LG_BF16_BTK - 1) / LG_BF16_BTK;
     const long long tl = (long long)nkt * sh.Hkv * sh.B;
-    const int total = (int)tl, per_xcd = (total + 7) / 8;
+    const int total = (int)tl, nbh = sh.Hkv * sh.B;
+    const int per_xcd = (total - nbh + 7) / 8;  // chunked items (all but key tile 0) per XCD
+    const dim3 grid(nbh + per_xcd * 8);
     if (sh.D == 64)
-      dkdv_bf16_kernel<64><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
+      dkdv_bf16_kernel<64><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
                                                             (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,
                                                             total, per_xcd);
     else
-      dkdv_bf16_kernel<128><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
+      dkdv_bf16_kernel<128><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
                                                              (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,
                                                              total, per_xcd);
     e = hipGetLastError();

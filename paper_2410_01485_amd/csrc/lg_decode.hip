@@ -18,7 +18,13 @@
 namespace {
 
 constexpr int WAVES = 4;
-constexpr int U = 4;  // key rows per lane group per iteration
+#ifndef LG_DEC_U
+#define LG_DEC_U 8
+#endif
+#ifndef LG_DEC_TARGET
+#define LG_DEC_TARGET 512
+#endif
+constexpr int U = LG_DEC_U;  // key rows per lane group per iteration
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float x) {
@@ -259,11 +265,12 @@ hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out
 
 }  // namespace
 
-// Enough workgroups to fill 256 CUs several times over, but at least 256 slots each
+// About two workgroups per CU (measured best at the 16 x 32 x 4160-slot workload: one
+// workgroup per (b, kv head), no merge pass), at least 256 slots each
 // and never an empty split.
 int lg_decode_splits(int B, int Hkv, int valid) {
   const long long pairs = (long long)B * Hkv;
-  long long want = (4096 + pairs - 1) / pairs;
+  long long want = (LG_DEC_TARGET + pairs - 1) / pairs;
   const long long cap = (valid + 255) / 256;
   if (want > cap) want = cap;
   if (want < 1) want = 1;

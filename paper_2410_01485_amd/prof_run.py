@@ -7,7 +7,7 @@ fwd / bwd   : B1 H32 D128 N131072 bf16, sink 64 + window 4096 (the training-step
 fwd_strided : B1 H32 D128 N32768 bf16, 64-token blocks: own + 2 preceding, sink block, every 8th
 fwd_gqa     : B1 Hq64/Hkv8 D128 N131072 bf16, sink 64 + window 4096
 decode      : B16 H32 D128 bf16, 64 + 4096 cache slots, three rotating cache sets
-copy        : a plain 1 GiB device-to-device copy (reads 2^30 bytes, writes 2^30 bytes): the yardstick
+copy        : a plain elementwise pass over 1 GiB (reads 2^30 bytes, writes 2^30 bytes): the yardstick
               that FETCH_SIZE / WRITE_SIZE counter readings are scaled by
 Inputs are filled on the device (values do not matter to a profile).
 """
@@ -31,10 +31,10 @@ def main():
         return torch.empty(*shape, device=dev, dtype=torch.float32).normal_().to(bf)
 
     if what == "copy":
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).zero_()
         b = torch.empty_like(a)
         for _ in range(reps):
-            b.copy_(a)
+            torch.add(a, 1.0, out=b)   # an elementwise kernel: reads 2^30 bytes, writes 2^30 bytes
     elif what in ("fwd", "bwd", "fwd_strided", "fwd_gqa"):
         Hq, Hkv, N, sink, window, block, stride = 32, 32, 131072, 64, 4096, 1, 0
         if what == "fwd_strided":
