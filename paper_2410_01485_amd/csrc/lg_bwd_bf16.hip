@@ -276,7 +276,11 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const int q0 = u_c * TQ;
     u_c = (u_c == hi) ? lo : u_c + 1;
     const int q1 = min(q0 + TQ - 1, N - 1);
-    const bool full = lg_tile_kind(m, q0, q1, k0 + wave * 32, k0 + wave * 32 + 31) == LG_TILE_FULL && q0 + TQ <= N;
+    // this wave's 32 keys against the step's 64 queries: a wave with no live pair sits the step
+    // out (most waves of the sink key tile do, once the queries are past its window)
+    const int kind = lg_tile_kind(m, q0, q1, k0 + wave * 32, k0 + wave * 32 + 31);
+    if (kind == LG_TILE_DEAD) continue;
+    const bool full = kind == LG_TILE_FULL && q0 + TQ <= N;
     const int sq = VRES + buf * STAGE, sg = sq + OFF_G;
     const float* sL = reinterpret_cast<const float*>(smem + sq + OFF_L);
     uint32_t bits = ~0u;
