@@ -61,6 +61,8 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
   const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
   const int i = q0 + wave * 32 + n;
   const int iq = min(i, N - 1);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int qw0 = min(q0 + wave_s * 32, N - 1), qw1 = min(q0 + wave_s * 32 + 31, N - 1);  // this wave's rows
 
   bf16x8_t qf[DC], gf[DC];
 #pragma unroll
@@ -114,16 +116,21 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
       ++ahead;
     }
     const int k0 = t * TK;
-    const bool full = lg_qsched_full(m, qs, t);
+    // A tile that is not live throughout for the workgroup's 256 rows is classified again for
+    // this wave's 32 rows: most waves then find it wholly live or wholly dead (they sit it out).
+    int kind = LG_TILE_FULL;
+    if (!lg_qsched_full(m, qs, t)) kind = lg_tile_kind(m, qw0, qw1, k0, k0 + TK - 1);
+    const bool full = kind == LG_TILE_FULL;
     const int sk = stage * STAGE, sv = sk + T::BYTES;
     uint32_t bits = 0xffffffffu;
-    if (!full) {
+    if (kind == LG_TILE_PARTIAL) {
       bits = 0;
 #pragma unroll 1
       for (int r = 0; r < 32; ++r)
         bits |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
     }
 
+    if (kind != LG_TILE_DEAD)
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16_t sc, dp;
@@ -211,6 +218,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
   const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
   const int j = k0 + wave * 32 + n;  // this lane's key
+  const int kw0 = k0 + __builtin_amdgcn_readfirstlane(wave) * 32;  // this wave's first key
   const int jk = min(j, N - 1);
 
   bf16x8_t kf[DC];
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const int q1 = min(q0 + TQ - 1, N - 1);
     // this wave's 32 keys against the step's 64 queries: a wave with no live pair sits the step
     // out (most waves of the sink key tile do, once the queries are past its window)
-    const int kind = lg_tile_kind(m, q0, q1, k0 + wave * 32, k0 + wave * 32 + 31);
+    const int kind = lg_tile_kind(m, q0, q1, kw0, kw0 + 31);
     if (kind == LG_TILE_DEAD) continue;
     const bool full = kind == LG_TILE_FULL && q0 + TQ <= N;
     const int sq = VRES + buf * STAGE, sg = sq + OFF_G;

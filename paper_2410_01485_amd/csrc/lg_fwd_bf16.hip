@@ -59,6 +59,8 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
   const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
   const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
   const int i = q0 + wave * 32 + n;  // this lane's query row
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int qw0 = min(q0 + wave_s * 32, N - 1), qw1 = min(q0 + wave_s * 32 + 31, N - 1);  // this wave's rows
 
   // Q fragments (B operand): lane (n, g) holds dims 16*dc + 8g .. +7 of its row.
   bf16x8_t qf[DC];
@@ -117,9 +119,14 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
     }
 
     const int k0 = t * TK;
-    const bool full = lg_qsched_full(m, qs, t);
+    // A tile that is not live throughout for the workgroup's 256 rows is classified again for
+    // this wave's 32 rows: most waves then find it wholly live or wholly dead (they sit it out).
+    int kind = LG_TILE_FULL;
+    if (!lg_qsched_full(m, qs, t)) kind = lg_tile_kind(m, qw0, qw1, k0, k0 + TK - 1);
+    const bool full = kind == LG_TILE_FULL;
     const int sk = stage * STAGE;   // byte offsets of the K and V tiles inside smem
     const int sv = sk + T::BYTES;
+    if (kind != LG_TILE_DEAD) {
 
     // ---- S^T = K Q^T ----
     f32x16_t sacc[2];
@@ -194,6 +201,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
     for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int db = 0; db < DB; ++db) oacc[db] = lg_mfma32(rd.read_cols(smem, sv, db, c), pf[c], oacc[db]);
+    }  // kind != dead
 
     --ahead;
     t = lg_qsched_next(m, qs, t);
