@@ -24,14 +24,26 @@ constexpr int NT = TQ * 2;      // threads: one wave per 32 rows
 constexpr int STAGES = 4;
 static_assert(TQ == 256 && TK == 64, "8 waves x 32 rows, 64-key tiles");
 
-template <int D>
+// TOKEN: the pattern is token-granular without strided columns (block <= 1, stride 0).  The
+// mask fields that are then known let the compiler drop the block / stride arithmetic from
+// the per-tile scheduler, and partial tiles are masked with two compares per element.
+template <int D, bool TOKEN>
 __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict__ q,
                                                       const uint16_t* __restrict__ k,
                                                       const uint16_t* __restrict__ v,
                                                       uint16_t* __restrict__ out,
                                                       float* __restrict__ lse, int Hq, int Hkv,
-                                                      float scale_log2e, LgMask m, int nqt,
+                                                      float scale_log2e, LgMask m_in, int nqt,
                                                       int total, int per_xcd) {
+  LgMask m = m_in;
+  if (TOKEN) {
+    m.b = 1;
+    m.stride = 0;
+    m.bshift = 0;
+    m.smask = -1;
+    m.sb = m.sink;
+    m.wb = m.window;
+  }
   using T = LgSwzTile<D>;
   using Dma = LgDma<D, NT>;
   constexpr int DC = D / 16;            // 16-wide contraction chunks of the head dim
@@ -140,7 +152,23 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
       for (int kb = 0; kb < 2; ++kb) sacc[kb] = lg_mfma32(rd.read_rows(smem, sk, kb, dc), qf[dc], sacc[kb]);
 
     // ---- online softmax (log2 domain) ----
-    if (!full) {
+    if (!full && TOKEN) {
+      // Row i sees the keys [i - window + 1, i] and the sink keys below min(sink, i + 1).  In
+      // tile coordinates (key = k0 + 4g + c, c a compile-time constant per register):
+      const int hi = i - k0 - 4 * g;           // c <= hi          : causal
+      const int lo = hi - (m.window - 1);      // c >= lo          : inside the window
+      const int se = m.sink - k0 - 4 * g;      // c < se (&& c <= hi): a sink key
+      const bool has_sink = k0 < m.sink;       // wave-uniform
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = 32 * kb + lg_crow(r, 0);
+          bool live = (unsigned)(c - lo) < (unsigned)m.window;
+          if (has_sink) live |= c < se && c <= hi;
+          if (!live) sacc[kb][r] = -INFINITY;
+        }
+    } else if (!full) {
       uint32_t bits = 0;
 #pragma unroll 1
       for (int r = 0; r < 32; ++r) {
@@ -238,11 +266,18 @@ hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void*
   const int per_xcd = (total + 7) / 8;
   const float sl2 = sh.scale * 1.44269504088896340736f;
   const dim3 grid(per_xcd * 8);
-  if (sh.D == 64)
-    fwd_bf16_kernel<64><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
-                                            (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
-  else
-    fwd_bf16_kernel<128><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
-                                             (uint16_t*)out, lse, sh.Hq, sh.Hkv, sl2, m, nqt, total, per_xcd);
+  const bool token = m.b == 1 && m.stride == 0;
+#define LG_FWD_LAUNCH(DD, TT)                                                                     \
+  fwd_bf16_kernel<DD, TT><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k,             \
+                                              (const uint16_t*)v, (uint16_t*)out, lse, sh.Hq,     \
+                                              sh.Hkv, sl2, m, nqt, total, per_xcd)
+  if (sh.D == 64) {
+    if (token) LG_FWD_LAUNCH(64, true);
+    else LG_FWD_LAUNCH(64, false);
+  } else {
+    if (token) LG_FWD_LAUNCH(128, true);
+    else LG_FWD_LAUNCH(128, false);
+  }
+#undef LG_FWD_LAUNCH
   return hipGetLastError();
 }

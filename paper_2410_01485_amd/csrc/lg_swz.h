@@ -59,7 +59,7 @@ struct LgDma {
       const int chunk = (p % T::CPR) ^ T::pi(row);
       voff[x] = row * T::ROW_BYTES + chunk * 16;
     }
-    wave_off = (tid & ~63) * 16;
+    wave_off = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6) * 1024u;  // wave-uniform: stays scalar
   }
   // src: first row of the tile in global memory (wave-uniform); rows_left: rows of the matrix
   // from there on (rows past the end are replaced by the last valid row); lds: LDS byte
@@ -73,8 +73,8 @@ struct LgDma {
         const int r = min(row, rows_left - 1);
         off = off - row * T::ROW_BYTES + r * T::ROW_BYTES;
       }
-      const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds + wave_off + x * NT * 16);
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(off), "s"(src)
+      const uint32_t m0 = lds + wave_off + x * NT * 16;  // all scalar
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(m0)), "v"(off), "s"(src)
                    : "memory");
     }
   }
