@@ -30,12 +30,26 @@ namespace {
 
 constexpr float LOG2E = 1.44269504088896340736f;
 
+// TOKEN (both kernels): the pattern is token-granular without strided columns (block <= 1,
+// stride 0).  The mask fields that are then known let the compiler drop the block / stride
+// arithmetic from the per-tile scheduling, and partial tiles are masked with two compares per
+// element instead of a per-element evaluation of the general predicate.
+
 // ------------------------------------------------------------------------- dq
-template <int D>
+template <int D, bool TOKEN>
 __global__ __launch_bounds__(512) void dq_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
-    uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m, int nqt, int total, int per_xcd) {
+    uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m_in, int nqt, int total, int per_xcd) {
+  LgMask m = m_in;
+  if (TOKEN) {
+    m.b = 1;
+    m.stride = 0;
+    m.bshift = 0;
+    m.smask = -1;
+    m.sb = m.sink;
+    m.wb = m.window;
+  }
   using T = LgSwzTile<D>;
   constexpr int NT = 512, STAGES = 4;
   using Dma = LgDma<D, NT>;
@@ -123,12 +137,25 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
     const bool full = kind == LG_TILE_FULL;
     const int sk = stage * STAGE, sv = sk + T::BYTES;
     uint32_t bits = 0xffffffffu;
-    if (kind == LG_TILE_PARTIAL) {
+    if (kind == LG_TILE_PARTIAL && !TOKEN) {
       bits = 0;
 #pragma unroll 1
       for (int r = 0; r < 32; ++r)
         bits |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
     }
+    // Token mode: row i sees the keys [i - window + 1, i] and the sink keys below
+    // min(sink, i + 1).  In tile coordinates (key = k0 + 4g + c, c a compile-time constant):
+    const int hi = i - k0 - 4 * g;         // c <= hi           : causal
+    const int lo = hi - (m.window - 1);    // c >= lo           : inside the window
+    const int se = m.sink - k0 - 4 * g;    // c < se (&& c <= hi): a sink key
+    const bool has_sink = k0 < m.sink;     // wave-uniform
+    auto dead = [&](int kb, int r) -> bool {
+      if (!TOKEN) return !(bits & (1u << (kb * 16 + r)));
+      const int c = 32 * kb + lg_crow(r, 0);
+      bool live = (unsigned)(c - lo) < (unsigned)m.window;
+      if (has_sink) live |= c < se && c <= hi;
+      return !live;
+    };
 
     if (kind != LG_TILE_DEAD)
 #pragma unroll
@@ -145,7 +172,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float p = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -lse2));
-        if (!full && !(bits & (1u << (kb * 16 + r)))) p = 0.f;
+        if (!full && dead(kb, r)) p = 0.f;
         ds[r] = p * (dp[r] - di);
       }
 #pragma unroll
@@ -174,12 +201,21 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------- dk, dv
-template <int D>
+template <int D, bool TOKEN>
 __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
-    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
     int nkt, int total, int per_xcd) {
+  LgMask m = m_in;
+  if (TOKEN) {
+    m.b = 1;
+    m.stride = 0;
+    m.bshift = 0;
+    m.smask = -1;
+    m.sb = m.sink;
+    m.wb = m.window;
+  }
   using T = LgSwzTile<D>;
   constexpr int NT = 512;
   using Dma = LgDma<D, NT>;
@@ -292,7 +328,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const int sq = VRES + buf * STAGE, sg = sq + OFF_G;
     const float* sL = reinterpret_cast<const float*>(smem + sq + OFF_L);
     uint32_t bits = ~0u;
-    if (!full) {
+    if (!full && !TOKEN) {
       bits = 0;
 #pragma unroll 1
       for (int r = 0; r < 32; ++r) {
@@ -300,6 +336,16 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
         bits |= (uint32_t)(i < N && lg_live(m, i, j)) << r;
       }
     }
+    // Token mode: key j is seen by the rows [j, j + window - 1] (by every row >= j if it is a
+    // sink key), below N.  In tile coordinates (row = q0 + 4g + c, c a compile-time constant):
+    const int lo_c = j - q0 - 4 * g;                                   // c >= lo_c : causal
+    const unsigned w_eff = j < m.sink ? 0x7fffffffu : (unsigned)m.window;  // c < lo_c + w_eff
+    const int n_c = N - q0 - 4 * g;                                    // c < n_c   : row exists
+    auto dead = [&](int qb, int r) -> bool {
+      if (!TOKEN) return !((bits >> (qb * 16 + r)) & 1);
+      const int c = 32 * qb + lg_crow(r, 0);
+      return !((unsigned)(c - lo_c) < w_eff && c < n_c);
+    };
 
     // Per 32-row query block, in an order that keeps few values alive at a time:
     // S -> P -> (dV += dO^T P) -> dP -> dS -> (dK += Q^T dS)
@@ -322,7 +368,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
           for (int t = 0; t < 4; ++t) {
             const int r = 4 * r4 + t;
             float pv = __builtin_amdgcn_exp2f(fmaf(sc[r], scale, -lv[t]) * LOG2E);
-            if (!full && !((bits >> (qb * 16 + r)) & 1)) pv = 0.f;
+            if (!full && dead(qb, r)) pv = 0.f;
             p[r] = pv;
           }
         }
@@ -391,17 +437,24 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
   const uint16_t* uk = (const uint16_t*)k;
   const uint16_t* uv = (const uint16_t*)v;
   const uint16_t* ug = (const uint16_t*)dout;
+  const bool token = m.b == 1 && m.stride == 0;
   {
     const int nqt = (sh.N + LG_BF16_TQ - 1) / LG_BF16_TQ;
     const long long tl = (long long)nqt * sh.Hq * sh.B;
     if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
     const int total = (int)tl, per_xcd = (total + 7) / 8;
-    if (sh.D == 64)
-      dq_bf16_kernel<64><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
-                                                          sh.Hkv, sh.scale, m, nqt, total, per_xcd);
-    else
-      dq_bf16_kernel<128><<<dim3(per_xcd * 8), 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq,
-                                                           sh.Hkv, sh.scale, m, nqt, total, per_xcd);
+    const dim3 grid(per_xcd * 8);
+#define LG_DQ_LAUNCH(DD, TT)                                                                        \
+  dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq, sh.Hkv, \
+                                              sh.scale, m, nqt, total, per_xcd)
+    if (sh.D == 64) {
+      if (token) LG_DQ_LAUNCH(64, true);
+      else LG_DQ_LAUNCH(64, false);
+    } else {
+      if (token) LG_DQ_LAUNCH(128, true);
+      else LG_DQ_LAUNCH(128, false);
+    }
+#undef LG_DQ_LAUNCH
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], s);
@@ -412,14 +465,18 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const int total = (int)tl, nbh = sh.Hkv * sh.B;
     const int per_xcd = (total - nbh + 7) / 8;  // chunked items (all but key tile 0) per XCD
     const dim3 grid(nbh + per_xcd * 8);
-    if (sh.D == 64)
-      dkdv_bf16_kernel<64><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
-                                                            (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,
-                                                            total, per_xcd);
-    else
-      dkdv_bf16_kernel<128><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,
-                                                             (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,
-                                                             total, per_xcd);
+#define LG_DKDV_LAUNCH(DD, TT)                                                                  \
+  dkdv_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,         \
+                                                (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,   \
+                                                total, per_xcd)
+    if (sh.D == 64) {
+      if (token) LG_DKDV_LAUNCH(64, true);
+      else LG_DKDV_LAUNCH(64, false);
+    } else {
+      if (token) LG_DKDV_LAUNCH(128, true);
+      else LG_DKDV_LAUNCH(128, false);
+    }
+#undef LG_DKDV_LAUNCH
     e = hipGetLastError();
     if (ev) (void)hipEventRecord(ev[3], s);
   }
