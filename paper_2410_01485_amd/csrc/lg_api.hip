@@ -106,7 +106,7 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
   if (kernel_ms) {
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     for (int x = 0; x < 3 && e == hipSuccess; ++x) e = hipEventElapsedTime(&kernel_ms[x], evs[x], evs[x + 1]);
-    for (int x = 0; x < 4; ++x) hipEventDestroy(evs[x]);
+    for (int x = 0; x < 4; ++x) (void)hipEventDestroy(evs[x]);
   }
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
 }

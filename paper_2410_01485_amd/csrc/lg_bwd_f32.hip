@@ -244,10 +244,10 @@ hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, con
                              void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
                              hipEvent_t* ev) {
   float* delta = (float*)ws;
-  if (ev) hipEventRecord(ev[0], s);
+  if (ev) (void)hipEventRecord(ev[0], s);
   hipError_t e = lg_launch_delta(dout, out, delta, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_F32, s);
   if (e != hipSuccess) return e;
-  if (ev) hipEventRecord(ev[1], s);
+  if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 gq((sh.N + LG_F32_TQ - 1) / LG_F32_TQ, sh.Hq, sh.B);
   const dim3 gk((sh.N + LG_F32_BTK - 1) / LG_F32_BTK, sh.Hkv, sh.B);
   if (sh.D == 64)
@@ -256,12 +256,12 @@ hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, con
     dq_f32_kernel<128><<<gq, 256, 0, s>>>(q, k, v, dout, lse, delta, dq, sh.Hq, sh.Hkv, sh.scale, m);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (ev) hipEventRecord(ev[2], s);
+  if (ev) (void)hipEventRecord(ev[2], s);
   if (sh.D == 64)
     dkdv_f32_kernel<64><<<gk, 256, 0, s>>>(q, k, v, dout, lse, delta, dk, dv, sh.Hq, sh.Hkv, sh.scale, m);
   else
     dkdv_f32_kernel<128><<<gk, 256, 0, s>>>(q, k, v, dout, lse, delta, dk, dv, sh.Hq, sh.Hkv, sh.scale, m);
   e = hipGetLastError();
-  if (ev) hipEventRecord(ev[3], s);
+  if (ev) (void)hipEventRecord(ev[3], s);
   return e;
 }
