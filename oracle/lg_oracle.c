@@ -63,6 +63,47 @@ long lgo_ring_slot(long p, long sink, long window) {
   return p < sink ? p : sink + (p - sink) % window;
 }
 
+/* Reduced KV cache of one (batch, kv head) for the general pattern (Section 3.2:
+ * a fixed cache-management rule instead of per-step token selection; Section 4.1:
+ * the block-sparse variant retains one block per `stride` blocks).  A cache row is
+ *   [ sink tokens | rolling window of `window` tokens | retained strided blocks ]
+ * and token p is kept
+ *   - in slot lgo_ring_slot(p)                       (always; the window part rolls), and
+ *   - if its block kb = p / b is a strided column (kb % stride == stride - 1), also in
+ *     slot sink + window + (kb / stride) * b + p % b (never overwritten).
+ * Returns that second slot, or -1 if the token's block is not retained. */
+long lgo_strided_slot(long p, long sink, long window, long block, long stride) {
+  long b = block > 1 ? block : 1;
+  long kb = p / b;
+  if (stride <= 0 || kb % stride != stride - 1) return -1;
+  return sink + window + (kb / stride) * b + p % b;
+}
+
+/* Slots a cache row needs for contexts of up to n_max tokens. */
+long lgo_cache_slots(long n_max, long sink, long window, long block, long stride) {
+  long b = block > 1 ? block : 1;
+  long nb = (n_max + b - 1) / b;
+  return sink + window + (stride > 0 ? (nb / stride) * b : 0);
+}
+
+/* Append the T tokens at positions pos .. pos+T-1 to the caches of `heads` (batch x kv
+ * head) rows: tokens are written one after the other in position order, each to the slot(s)
+ * above, a later token overwriting an earlier one that mapped to the same ring slot.
+ * rows_new: [heads, T, row_bytes]; cache: [heads, cache_slots, row_bytes]; bytes are
+ * copied as they are. */
+void lgo_ring_append(const unsigned char* rows_new, unsigned char* cache, long heads, long T, long pos,
+                     long row_bytes, long cache_slots, long sink, long window, long block, long stride) {
+  for (long h = 0; h < heads; ++h)
+    for (long t = 0; t < T; ++t) {
+      const long p = pos + t;
+      const unsigned char* src = rows_new + (h * T + t) * row_bytes;
+      unsigned char* row = cache + h * cache_slots * row_bytes;
+      memcpy(row + lgo_ring_slot(p, sink, window) * row_bytes, src, (size_t)row_bytes);
+      const long ss = lgo_strided_slot(p, sink, window, block, stride);
+      if (ss >= 0 && ss < cache_slots) memcpy(row + ss * row_bytes, src, (size_t)row_bytes);
+    }
+}
+
 int lgo_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -43,6 +43,12 @@ def _load():
         L.lgo_row_count.restype = lng
         L.lgo_ring_slot.argtypes = [lng] * 3
         L.lgo_ring_slot.restype = lng
+        L.lgo_strided_slot.argtypes = [lng] * 5
+        L.lgo_strided_slot.restype = lng
+        L.lgo_cache_slots.argtypes = [lng] * 5
+        L.lgo_cache_slots.restype = lng
+        L.lgo_ring_append.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [lng] * 9
+        L.lgo_ring_append.restype = None
         L.lgo_threads.argtypes = []
         L.lgo_threads.restype = ctypes.c_int
         L.lgo_fwd.argtypes = [fp, fp, fp, dp, dp] + [lng] * 9 + [dbl, lng, lng]
@@ -87,6 +93,27 @@ def row_count(i, sink, window, block=1, stride=0):
 
 def ring_slot(p, sink, window):
     return int(_load().lgo_ring_slot(p, sink, window))
+
+
+def strided_slot(p, sink, window, block=1, stride=0):
+    """Slot of token p in the retained-strided-blocks part of a cache row, or -1."""
+    return int(_load().lgo_strided_slot(p, sink, window, block, stride))
+
+
+def cache_slots(n_max, sink, window, block=1, stride=0):
+    return int(_load().lgo_cache_slots(n_max, sink, window, block, stride))
+
+
+def ring_append(rows_new, cache, pos, sink, window, block=1, stride=0):
+    """Append rows_new [B,Hkv,T,D] (positions pos..pos+T-1) to cache [B,Hkv,slots,D] in place.
+    Any dtype; bytes are copied."""
+    rows_new = np.ascontiguousarray(rows_new)
+    assert cache.flags["C_CONTIGUOUS"] and cache.dtype == rows_new.dtype
+    B, H, T, D = rows_new.shape
+    assert cache.shape[:2] == (B, H) and cache.shape[3] == D
+    _load().lgo_ring_append(rows_new.ctypes.data, cache.ctypes.data, B * H, T, pos,
+                            D * rows_new.dtype.itemsize, cache.shape[2], sink, window, block, stride)
+    return cache
 
 
 def _scale(scale, D):
