@@ -64,8 +64,9 @@
  *                       stride < 0; block > 1 with sink % block != 0 or
  *                       window % block != 0; a pointer not 16-byte aligned;
  *                       B*H*N*D beyond 2^40 elements
- *   LG_ERR_UNSUPPORTED  D not in {64, 128}; dtype not in lg_dtype; decode with
- *                       stride > 0 or block > 1; Hq/Hkv > 16 in decode
+ *   LG_ERR_UNSUPPORTED  D not in {64, 128}; dtype not in lg_dtype; lg_sparse_attn_decode
+ *                       with stride > 0 (use lg_sparse_attn_decode_cache); Hq/Hkv > 16
+ *                       in decode
  *   LG_ERR_WORKSPACE    workspace NULL or smaller than *_workspace_bytes
  *   LG_ERR_LAUNCH       the HIP runtime reported an error at launch (no GPU,
  *                       wrong architecture, ...)
@@ -146,8 +147,10 @@ int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const vo
  * Cache slot map: token p lives in slot p when p < sink, otherwise in slot
  * sink + ((p - sink) % window).  The first min(N, sink+window) slots are valid;
  * they hold exactly the keys j with live(N-1, j), so the result equals row N-1
- * of lg_sparse_attn_fwd on the whole context.  Token-granular pattern only
- * (block <= 1, stride == 0).
+ * of lg_sparse_attn_fwd on the whole context.  stride must be 0 here (a strided pattern
+ * needs the retained-block part of the cache: lg_sparse_attn_decode_cache below); with
+ * block > 1 the part of the ring that belongs to the block that just left the window is
+ * skipped.
  * workspace holds float32 partial results of the split over cache slots.
  */
 size_t lg_sparse_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
@@ -157,6 +160,49 @@ int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cach
                           int B, int Hq, int Hkv, int N, int D,
                           int sink, int window, int block, int stride,
                           int dtype, float scale, void* hip_stream);
+
+/*
+ * Reduced KV cache for every pattern (Section 3.2: a fixed cache-management rule, no per-step
+ * token selection; Section 4.1: the block-sparse variant keeps one block per `stride` blocks,
+ * about 2K tokens at 128K).  A cache row [cache_slots, D] of one (b, kv head) is laid out as
+ *     [ sink tokens | rolling window of `window` tokens | retained strided blocks ]
+ * Token p is stored in slot p when p < sink, otherwise in slot sink + ((p - sink) % window);
+ * when its block kb = p / max(block,1) is a strided column (stride > 0 and
+ * kb % stride == stride - 1) it is also stored in slot
+ * sink + window + (kb / stride) * max(block,1) + p % max(block,1), which is never reused.
+ *
+ * lg_kv_cache_slots: slots a row needs for contexts of up to n_max tokens
+ *   (sink + window when stride == 0); 0 if the arguments are invalid.
+ * lg_kv_ring_append: stores the T tokens at positions pos .. pos+T-1.
+ *   k_new, v_new : [B, Hkv, T, D] device;  k_cache, v_cache : [B, Hkv, cache_slots, D] device,
+ *   updated in place (other slots keep their contents).  The result is what storing the tokens
+ *   one by one in position order would give.  T = N, pos = 0 builds the cache after a prefill.
+ *   LG_ERR_INVALID_ARG also when T < 1, pos < 0, or cache_slots < lg_kv_cache_slots(pos + T, ...).
+ * lg_sparse_attn_decode_cache: decode (as lg_sparse_attn_decode: the query is token N-1, its
+ *   own k/v already appended) for any pattern, over caches [B, Hkv, cache_slots, D] with
+ *   cache_slots >= lg_kv_cache_slots(N, ...).  Reads the sink slots, the live part of the
+ *   rolling window and the retained blocks older than the window, each live key once; equals
+ *   row N-1 of lg_sparse_attn_fwd on the whole context.  lg_sparse_attn_decode is this call
+ *   with cache_slots = sink + window (stride == 0).
+ */
+size_t lg_kv_cache_slots(int n_max, int sink, int window, int block, int stride);
+int lg_kv_ring_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                      int B, int Hkv, int D, int T, int pos, int cache_slots,
+                      int sink, int window, int block, int stride, int dtype, void* hip_stream);
+size_t lg_sparse_attn_decode_cache_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                                   int sink, int window, int block, int stride, int dtype);
+int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                float* lse, void* workspace, size_t workspace_bytes,
+                                int B, int Hq, int Hkv, int N, int D,
+                                int sink, int window, int block, int stride, int cache_slots,
+                                int dtype, float scale, void* hip_stream);
+/*
+ * Host-only: the runs of consecutive cache slots a decode step at context length N reads
+ * (at most 4; start/len are HOST arrays of 4 entries; *nseg receives the count).  Runs the
+ * same source the decode launch uses (no GPU needed).
+ */
+int lg_debug_decode_segments(int N, int sink, int window, int block, int stride,
+                             int* nseg, int32_t* start, int32_t* len);
 
 /*
  * Host-only view of the block-skipping tile scheduler (Section 3.2: the mask is

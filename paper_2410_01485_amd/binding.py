@@ -47,6 +47,16 @@ def lib():
         L.lg_sparse_attn_decode_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
         L.lg_sparse_attn_decode.restype = _i
+        L.lg_kv_cache_slots.argtypes = [_i] * 5
+        L.lg_kv_cache_slots.restype = _sz
+        L.lg_kv_ring_append.argtypes = [_vp] * 4 + [_i] * 11 + [_vp]
+        L.lg_kv_ring_append.restype = _i
+        L.lg_sparse_attn_decode_cache_workspace_bytes.argtypes = [_i] * 10
+        L.lg_sparse_attn_decode_cache_workspace_bytes.restype = _sz
+        L.lg_sparse_attn_decode_cache.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 10 + [_i, _f, _vp]
+        L.lg_sparse_attn_decode_cache.restype = _i
+        L.lg_debug_decode_segments.argtypes = [_i] * 5 + [ctypes.POINTER(_i), _vp, _vp]
+        L.lg_debug_decode_segments.restype = _i
         L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
                                                    _vp, _vp, _sz, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
         L.lg_debug_tile_map.restype = _i
@@ -152,6 +162,60 @@ def lg_sparse_attn_decode(q, k_cache, v_cache, out, lse, workspace, N, sink, win
                                      _stream(q))
     if st != 0:
         raise LgError(st, "lg_sparse_attn_decode")
+
+
+def lg_kv_cache_slots(n_max, sink, window, block=1, stride=0):
+    """Slots per cache row for contexts of up to n_max tokens (0 if the arguments are invalid)."""
+    return int(lib().lg_kv_cache_slots(n_max, sink, window, block, stride))
+
+
+def lg_kv_ring_append(k_new, v_new, k_cache, v_cache, pos, sink, window, block=1, stride=0):
+    """Store k_new, v_new [B,Hkv,T,D] (positions pos..pos+T-1) into caches [B,Hkv,slots,D] in place."""
+    B, Hkv, T, D = k_new.shape
+    slots = k_cache.shape[2]
+    _check(v_new, B, Hkv, T, D), _check(k_new, B, Hkv, T, D)
+    _check(k_cache, B, Hkv, slots, D), _check(v_cache, B, Hkv, slots, D)
+    if k_cache.dtype != k_new.dtype or v_cache.dtype != k_new.dtype or v_new.dtype != k_new.dtype:
+        raise TypeError("caches and new rows must share one dtype")
+    st = lib().lg_kv_ring_append(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), B, Hkv, D, T, pos, slots,
+                                 sink, window, block, stride, _dtype_code(k_new), _stream(k_new))
+    if st != 0:
+        raise LgError(st, "lg_kv_ring_append")
+
+
+def decode_cache_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, dtype):
+    return int(lib().lg_sparse_attn_decode_cache_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride,
+                                                                 dtype))
+
+
+def lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, workspace, N, sink, window, block=1, stride=0,
+                                scale=0.0):
+    """out, lse <- one-token attention of q [B,Hq,D] over caches [B,Hkv,slots,D] of any pattern."""
+    B, Hq, D = q.shape
+    Hkv, slots = k_cache.shape[1], k_cache.shape[2]
+    _check(k_cache, B, Hkv, slots, D), _check(v_cache, B, Hkv, slots, D), _check(out, B, Hq, D)
+    if lse is not None:
+        _check(lse, B, Hq)
+    st = lib().lg_sparse_attn_decode_cache(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
+                                           _ptr(workspace),
+                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                           B, Hq, Hkv, N, D, sink, window, block, stride, slots, _dtype_code(q),
+                                           scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_decode_cache")
+
+
+def lg_debug_decode_segments(N, sink, window, block=1, stride=0):
+    """Host-only: [(first slot, length), ...] of the slot runs a decode step at context N reads."""
+    import numpy as np
+    n = _i(0)
+    start = np.zeros(4, dtype=np.int32)
+    length = np.zeros(4, dtype=np.int32)
+    st = lib().lg_debug_decode_segments(N, sink, window, block, stride, ctypes.byref(n), start.ctypes.data,
+                                        length.ctypes.data)
+    if st != 0:
+        raise LgError(st, "lg_debug_decode_segments")
+    return [(int(start[x]), int(length[x])) for x in range(n.value)]
 
 
 def lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed):

@@ -136,17 +136,70 @@ static int check_decode(int B, int Hq, int Hkv, int N, int D, int sink, int wind
                         int stride, int dtype) {
   int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
   if (st != LG_OK) return st;
-  if (stride > 0 || block > 1) return LG_ERR_UNSUPPORTED;
   if (Hq / Hkv > 16) return LG_ERR_UNSUPPORTED;
   if ((double)sink + (double)window > 1073741824.0) return LG_ERR_INVALID_ARG;
   return LG_OK;
 }
 
+size_t lg_kv_cache_slots(int n_max, int sink, int window, int block, int stride) {
+  if (check_common(1, 1, 1, n_max, 64, sink, window, block, stride, LG_F32) != LG_OK) return 0;
+  if ((double)sink + (double)window > 1073741824.0) return 0;
+  const long long c = lg_cache_slots(n_max, lg_make_cache_mask(n_max, sink, window, block, stride));
+  return c > 0x7fffffffLL ? 0 : (size_t)c;
+}
+
+int lg_kv_ring_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                      int B, int Hkv, int D, int T, int pos, int cache_slots,
+                      int sink, int window, int block, int stride, int dtype, void* hip_stream) {
+  if (!k_new || !v_new || !k_cache || !v_cache) return LG_ERR_NULL;
+  if (T < 1 || pos < 0 || (long long)pos + T > 0x7fffffffLL) return LG_ERR_INVALID_ARG;
+  int st = check_common(B, Hkv, Hkv, pos + T, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  const size_t need = lg_kv_cache_slots(pos + T, sink, window, block, stride);
+  if (need == 0 || cache_slots < 0 || (size_t)cache_slots < need) return LG_ERR_INVALID_ARG;
+  if ((double)B * Hkv * (double)cache_slots * D > 1099511627776.0) return LG_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+    return LG_ERR_INVALID_ARG;
+  const LgMask m = lg_make_cache_mask(pos + T, sink, window, block, stride);
+  const int row_bytes = D * (dtype == LG_F32 ? 4 : 2);
+  hipError_t e = lg_launch_kv_append(k_new, v_new, k_cache, v_cache, B, Hkv, row_bytes, T, pos, cache_slots,
+                                     m, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+size_t lg_sparse_attn_decode_cache_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
+                                                   int sink, int window, int block, int stride, int dtype) {
+  if (check_decode(B, Hq, Hkv, N, D, sink, window, block, stride, dtype) != LG_OK) return 0;
+  const LgDecSegs g = lg_decode_segments(lg_make_cache_mask(N, sink, window, block, stride));
+  return lg_decode_workspace_bytes(B, Hq, Hkv, D, g.pre[g.n]);
+}
+
+int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                float* lse, void* workspace, size_t workspace_bytes,
+                                int B, int Hq, int Hkv, int N, int D,
+                                int sink, int window, int block, int stride, int cache_slots,
+                                int dtype, float scale, void* hip_stream) {
+  if (!q || !k_cache || !v_cache || !out) return LG_ERR_NULL;
+  int st = check_decode(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  const size_t slots_needed = lg_kv_cache_slots(N, sink, window, block, stride);
+  if (slots_needed == 0 || cache_slots < 0 || (size_t)cache_slots < slots_needed) return LG_ERR_INVALID_ARG;
+  if ((double)B * Hkv * (double)cache_slots * D > 1099511627776.0) return LG_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      !aligned16(lse) || !aligned16(workspace))
+    return LG_ERR_INVALID_ARG;
+  const LgDecSegs g = lg_decode_segments(lg_make_cache_mask(N, sink, window, block, stride));
+  const size_t need = lg_decode_workspace_bytes(B, Hq, Hkv, D, g.pre[g.n]);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LG_ERR_WORKSPACE;
+  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
+  hipError_t e = lg_launch_decode(q, k_cache, v_cache, out, lse, workspace, B, Hq, Hkv, cache_slots, g, D,
+                                  dtype, sh.scale, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
 size_t lg_sparse_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
                                              int sink, int window, int dtype) {
-  if (check_decode(B, Hq, Hkv, N, D, sink, window, 1, 0, dtype) != LG_OK) return 0;
-  const int C = sink + window;
-  return lg_decode_workspace_bytes(B, Hq, Hkv, D, N < C ? N : C);
+  return lg_sparse_attn_decode_cache_workspace_bytes(B, Hq, Hkv, N, D, sink, window, 1, 0, dtype);
 }
 
 int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
@@ -157,17 +210,23 @@ int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cach
   if (!q || !k_cache || !v_cache || !out) return LG_ERR_NULL;
   int st = check_decode(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
   if (st != LG_OK) return st;
-  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
-      !aligned16(lse) || !aligned16(workspace))
-    return LG_ERR_INVALID_ARG;
-  const int C = sink + window;
-  const int valid = N < C ? N : C;
-  const size_t need = lg_decode_workspace_bytes(B, Hq, Hkv, D, valid);
-  if (need > 0 && (!workspace || workspace_bytes < need)) return LG_ERR_WORKSPACE;
-  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
-  hipError_t e = lg_launch_decode(q, k_cache, v_cache, out, lse, workspace, B, Hq, Hkv, C, valid, D,
-                                  dtype, sh.scale, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+  if (stride > 0) return LG_ERR_UNSUPPORTED;  // needs the retained-block part of the cache
+  return lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, workspace, workspace_bytes, B, Hq, Hkv, N,
+                                     D, sink, window, block, stride, sink + window, dtype, scale, hip_stream);
+}
+
+int lg_debug_decode_segments(int N, int sink, int window, int block, int stride,
+                             int* nseg, int32_t* start, int32_t* len) {
+  if (!nseg || !start || !len) return LG_ERR_NULL;
+  int st = check_decode(1, 1, 1, N, 64, sink, window, block, stride, LG_F32);
+  if (st != LG_OK) return st;
+  const LgDecSegs g = lg_decode_segments(lg_make_cache_mask(N, sink, window, block, stride));
+  *nseg = g.n;
+  for (int x = 0; x < 4; ++x) {
+    start[x] = x < g.n ? g.start[x] : 0;
+    len[x] = x < g.n ? g.pre[x + 1] - g.pre[x] : 0;
+  }
+  return LG_OK;
 }
 
 int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dtype, int transposed,

@@ -10,10 +10,18 @@
 // is filled even for small batches; a second tiny kernel merges the partial
 // (max, sum, accumulator) triples.  All query heads of a kv head are served by the
 // same pass over K/V (GQA).
+//
+// The keys of a step are up to four runs of consecutive slots (LgDecSegs: sink tokens,
+// live part of the rolling window, retained strided blocks); the kernel walks their
+// concatenation.  The common case, one run starting at slot 0, has its own instance
+// without the index translation.
+//
+// lg_kv_append_kernel stores new tokens into the cache rows by the same layout rule.
 #include <hip/hip_bf16.h>
 
 #include "../../include/longgen_attn.h"
 #include "lg_kernels.h"
+#include "lg_mask.h"
 
 namespace {
 
@@ -75,14 +83,14 @@ __device__ __forceinline__ void store_out(__hip_bfloat16* p, float x) { *p = __f
 
 // Partial record in the workspace, per (b, hq, split): D accumulators, max, sum
 // (max and running values are in the log2 domain: score * scale * log2(e)).
-template <typename T, int D, int GT>
+template <typename T, int D, int GT, bool SEGS>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict__ q,
                                                             const T* __restrict__ kc,
                                                             const T* __restrict__ vc,
                                                             T* __restrict__ out, float* __restrict__ lse,
                                                             float* __restrict__ ws, int Hq, int Hkv,
                                                             int C, int valid, int chunk, int splits,
-                                                            float scale_log2e) {
+                                                            float scale_log2e, LgDecSegs segs) {
   constexpr int E = 16 / sizeof(T);      // elements per 16-byte lane load
   constexpr int LPR = D / E;             // lanes per key row
   constexpr int KPW = 64 / LPR;          // key rows per wave per load
@@ -122,9 +130,17 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int slot = base + u * GROUPS + grp;
-      ok[u] = slot < s1;
-      const size_t off = (size_t)(ok[u] ? slot : s1 - 1) * D;
+      const int key = base + u * GROUPS + grp;  // index into the concatenated runs
+      ok[u] = key < s1;
+      int slot = ok[u] ? key : s1 - 1;
+      if (SEGS) {
+        int shift = segs.start[0];
+        if (slot >= segs.pre[1]) shift = segs.start[1] - segs.pre[1];
+        if (slot >= segs.pre[2]) shift = segs.start[2] - segs.pre[2];
+        if (slot >= segs.pre[3]) shift = segs.start[3] - segs.pre[3];
+        slot += shift;
+      }
+      const size_t off = (size_t)slot * D;
       Frag<T, E>::load(kbase + off, kf[u]);
       Frag<T, E>::load(vbase + off, vf[u]);
     }
@@ -237,9 +253,42 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(const float* __restrict
   if (lse != nullptr && d == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
 }
 
+// One thread per 16 bytes of a new token row (K and V): the token goes to its sink or ring
+// slot unless a later token of the same call lands on that ring slot, and to its retained-block
+// slot when its block is a strided column.  No two threads write the same bytes.
+template <int LPR>
+__global__ __launch_bounds__(256) void lg_kv_append_kernel(const uint4* __restrict__ kn,
+                                                           const uint4* __restrict__ vn,
+                                                           uint4* __restrict__ kc, uint4* __restrict__ vc,
+                                                           int T, int pos, int slots, LgMask m) {
+  const int ti = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  if (ti >= T) return;
+  const int c = threadIdx.x % LPR;
+  const size_t head = (size_t)blockIdx.z * gridDim.y + blockIdx.y;
+  const size_t src = (head * T + ti) * LPR + c;
+  const uint4 kx = kn[src], vx = vn[src];
+  const int p = pos + ti, last = pos + T - 1;
+  const size_t row0 = head * slots;
+  if (p < m.sink || (long long)p + m.window > last) {
+    const int slot = p < m.sink ? p : m.sink + (p - m.sink) % m.window;
+    kc[(row0 + slot) * LPR + c] = kx;
+    vc[(row0 + slot) * LPR + c] = vx;
+  }
+  if (m.stride > 0) {
+    const int kb = lg_div_b(m, p);
+    if (lg_strided(m, kb)) {
+      const int slot = m.sink + m.window + (kb / m.stride) * m.b + (p - kb * m.b);
+      kc[(row0 + slot) * LPR + c] = kx;
+      vc[(row0 + slot) * LPR + c] = vx;
+    }
+  }
+}
+
 template <typename T, int D>
 hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out, float* lse, void* ws,
-                        int B, int Hq, int Hkv, int C, int valid, float scale, hipStream_t s) {
+                        int B, int Hq, int Hkv, int C, const LgDecSegs& segs, float scale, hipStream_t s) {
+  const int valid = segs.pre[segs.n];
+  const bool plain = segs.n == 1 && segs.start[0] == 0;
   const int G = Hq / Hkv;
   const int splits = lg_decode_splits(B, Hkv, valid);
   const int chunk = (valid + splits - 1) / splits;
@@ -249,9 +298,16 @@ hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out
   const T* tv = (const T*)vc;
   T* to = (T*)out;
   float* fws = (float*)ws;
-#define LG_DECODE_LAUNCH(GT)                                                                     \
-  decode_kernel<T, D, GT><<<dim3(splits, Hkv*((G + GT - 1) / GT), B), WAVES * 64, 0, s>>>(       \
-      tq, tk, tv, to, lse, fws, Hq, Hkv, C, valid, chunk, splits, sl2)
+#define LG_DECODE_LAUNCH(GT)                                                                          \
+  do {                                                                                                \
+    const dim3 grid(splits, Hkv*((G + GT - 1) / GT), B);                                              \
+    if (plain)                                                                                        \
+      decode_kernel<T, D, GT, false><<<grid, WAVES * 64, 0, s>>>(tq, tk, tv, to, lse, fws, Hq, Hkv, C, \
+                                                                 valid, chunk, splits, sl2, segs);    \
+    else                                                                                              \
+      decode_kernel<T, D, GT, true><<<grid, WAVES * 64, 0, s>>>(tq, tk, tv, to, lse, fws, Hq, Hkv, C,  \
+                                                                valid, chunk, splits, sl2, segs);     \
+  } while (0)
   if (G == 1) LG_DECODE_LAUNCH(1);
   else if (G == 2) LG_DECODE_LAUNCH(2);
   else if (G <= 4) LG_DECODE_LAUNCH(4);
@@ -285,13 +341,28 @@ size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid) {
 }
 
 hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
-                            void* ws, int B, int Hq, int Hkv, int C, int valid, int D, int dtype,
-                            float scale, hipStream_t s) {
+                            void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
+                            int dtype, float scale, hipStream_t s) {
   if (dtype == LG_F32) {
-    return D == 64 ? launch_typed<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
-                   : launch_typed<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
+    return D == 64 ? launch_typed<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s)
+                   : launch_typed<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s);
   }
   return D == 64
-      ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
-      : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
+      ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s)
+      : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s);
+}
+
+hipError_t lg_launch_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                               int B, int Hkv, int row_bytes, int T, int pos, int slots,
+                               const LgMask& m, hipStream_t s) {
+  const int lpr = row_bytes / 16;  // 8, 16 or 32 lanes per token row
+  const dim3 grid((T + 256 / lpr - 1) / (256 / lpr), Hkv, B);
+  const uint4* kn = (const uint4*)k_new;
+  const uint4* vn = (const uint4*)v_new;
+  uint4* kc = (uint4*)k_cache;
+  uint4* vc = (uint4*)v_cache;
+  if (lpr == 8) lg_kv_append_kernel<8><<<grid, 256, 0, s>>>(kn, vn, kc, vc, T, pos, slots, m);
+  else if (lpr == 16) lg_kv_append_kernel<16><<<grid, 256, 0, s>>>(kn, vn, kc, vc, T, pos, slots, m);
+  else lg_kv_append_kernel<32><<<grid, 256, 0, s>>>(kn, vn, kc, vc, T, pos, slots, m);
+  return hipGetLastError();
 }

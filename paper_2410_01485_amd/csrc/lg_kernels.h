@@ -49,7 +49,10 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
 int lg_decode_splits(int B, int Hkv, int valid);
 size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid);
 hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
-                            void* ws, int B, int Hq, int Hkv, int C, int valid, int D,
+                            void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
                             int dtype, float scale, hipStream_t s);
+hipError_t lg_launch_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                               int B, int Hkv, int row_bytes, int T, int pos, int slots,
+                               const LgMask& m, hipStream_t s);
 
 #endif  // LG_KERNELS_H_

@@ -201,4 +201,91 @@ LG_HD void lg_qtile_range(const LgMask& m, int k0, int k1, int Tq, int* lo, int*
   *hi = (int)(last / Tq);
 }
 
+// ---------------------------------------------------------------------------------
+// Reduced KV cache (paper Section 3.2: fixed cache management; Section 4.1: the block-sparse
+// variant retains one block per `stride` blocks).  A cache row is
+//     [ sink tokens | rolling window of `window` tokens | retained strided blocks ]
+// token p sits in slot p (p < sink) or sink + (p - sink) % window, and, when its block
+// kb = p / b is a strided column, also in slot sink + window + (kb / stride) * b + p % b.
+//
+// The keys of a decode step (query = token N-1) are then up to four runs of consecutive
+// slots: the sink tokens, the live part of the rolling window (one or two runs: the ring
+// wraps, and in block mode the tail of the block that just left the window is still in the
+// ring but dead), and the retained blocks older than the window.  Every live key is in
+// exactly one run.
+struct LgDecSegs {
+  int n;         // runs in use
+  int start[4];  // first slot of a run
+  int pre[5];    // keys before a run; pre[n] = all keys of the step
+};
+
+LG_HD void lg_decsegs_push(LgDecSegs& g, int start, int len) {
+  if (len <= 0) return;
+  if (g.n > 0 && g.start[g.n - 1] + (g.pre[g.n] - g.pre[g.n - 1]) == start) {  // continues the previous run
+    g.pre[g.n] += len;
+    return;
+  }
+  g.start[g.n] = start;
+  g.pre[g.n + 1] = g.pre[g.n] + len;
+  ++g.n;
+}
+
+// The pattern for cache geometry: like lg_make_mask but sink and window keep their given
+// values (the slot layout depends on them, not on the current context length N).
+LG_HD LgMask lg_make_cache_mask(int N, int sink, int window, int block, int stride) {
+  LgMask m;
+  m.N = N;
+  m.b = block > 1 ? block : 1;
+  m.sb = sink / m.b;
+  m.wb = window / m.b;
+  m.sink = m.sb * m.b;
+  m.window = m.wb * m.b;
+  m.stride = stride > 0 ? stride : 0;
+  m.bshift = lg_log2_exact(m.b);
+  m.smask = (m.stride > 0 && lg_log2_exact(m.stride) >= 0) ? m.stride - 1 : -1;
+  return m;
+}
+
+// m: from lg_make_cache_mask, m.N = context length (>= 1), m.window >= 1.
+LG_HD LgDecSegs lg_decode_segments(const LgMask& m) {
+  LgDecSegs g;
+  g.n = 0;
+  for (int x = 0; x < 4; ++x) g.start[x] = 0;
+  for (int x = 0; x < 5; ++x) g.pre[x] = 0;
+  const int t = m.N - 1, qb = lg_div_b(m, t);
+  lg_decsegs_push(g, 0, m.N < m.sink ? m.N : m.sink);
+  if (m.N > m.sink) {
+    const long long w0 = ((long long)qb - m.wb + 1) * m.b;  // first token of the oldest live window block
+    const int pl = w0 > m.sink ? (int)w0 : m.sink;          // first token read from the ring
+    const int len = t - pl + 1;
+    if (len >= m.window) {
+      lg_decsegs_push(g, m.sink, m.window);  // the whole ring
+    } else {
+      const int r0 = (pl - m.sink) % m.window;
+      if (r0 + len <= m.window) {
+        lg_decsegs_push(g, m.sink + r0, len);
+      } else {
+        lg_decsegs_push(g, m.sink, r0 + len - m.window);
+        lg_decsegs_push(g, m.sink + r0, m.window - r0);
+      }
+    }
+  }
+  if (m.stride > 0) {
+    const int x_lo = m.sb / m.stride;  // first retained block that is not a sink block
+    const int hi_kb = qb - m.wb;       // newest block older than the window
+    if (hi_kb >= m.stride - 1) {
+      const int x_hi = (hi_kb - (m.stride - 1)) / m.stride;
+      if (x_hi >= x_lo) lg_decsegs_push(g, m.sink + m.window + x_lo * m.b, (x_hi - x_lo + 1) * m.b);
+    }
+  }
+  for (int x = g.n + 1; x < 5; ++x) g.pre[x] = 0x7fffffff;  // no key index reaches an unused run
+  return g;
+}
+
+// Slots a cache row needs for contexts of up to n_max tokens.
+LG_HD long long lg_cache_slots(int n_max, const LgMask& m) {
+  const long long nb = ((long long)n_max + m.b - 1) / m.b;
+  return (long long)m.sink + m.window + (m.stride > 0 ? (nb / m.stride) * m.b : 0);
+}
+
 #endif  // LG_MASK_H_
