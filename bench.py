@@ -163,6 +163,34 @@ def main():
                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4),
                            "traffic": sum(MEASURED_HBM_BYTES["decode_kernel"])}}
 
+    # the block-sparse + sink + window pattern of Section 4.1 over the same cache tensors:
+    # 64-token blocks, 1 sink block, 32 local blocks, one retained block per 64 (4160 slots too)
+    pb, ps, pwin, pstr = 64, 64, 2048, 64
+    assert lg.lg_kv_cache_slots(dN, ps, pwin, pb, pstr) == C
+    keys = sum(n for _, n in lg.lg_debug_decode_segments(dN, ps, pwin, pb, pstr))
+    need = lg.decode_cache_workspace_bytes(dB, dH, dH, dN, D, ps, pwin, pb, pstr, lg.LG_BF16)
+    pws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+    def pstep():
+        a, b_, c_ = sets[it[0] % 3]
+        it[0] += 1
+        lg.lg_sparse_attn_decode_cache(a, b_, c_, dout, dlse, pws, dN, ps, pwin, pb, pstr)
+
+    for _ in range(3):
+        pstep()
+    e0.record()
+    for _ in range(reps):
+        pstep()
+    e1.record()
+    torch.cuda.synchronize()
+    p_ms = e0.elapsed_time(e1) / reps
+    p_bytes = 2.0 * dB * dH * keys * D * 2 + 2.0 * dB * dH * D * 2
+    decode["block_sparse"] = {"workload": "same caches, block 64: 1 sink block + 32 local blocks + every 64th "
+                                          "block (%d of %d slots live)" % (keys, C),
+                              "us_per_call": round(p_ms * 1e3, 2), "bytes": p_bytes,
+                              "gbs": round(p_bytes / (p_ms * 1e-3) / 1e9, 1),
+                              "frac": round(p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
     # ------------------------------------------------------------------ CPU oracle baseline
     cpu = None
     if not args.no_cpu_baseline:
