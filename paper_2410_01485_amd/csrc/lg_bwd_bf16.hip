@@ -201,12 +201,45 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------- dk, dv
-template <int D, bool TOKEN>
+// Column keys (sink tokens, keys of strided block columns) are seen by every later query.
+// The query range of a key tile therefore has a dense window part (like every tile) and, if it
+// holds column keys, a long column part: all later rows, but only its column keys live.
+// With one column group per head (the sink of a sink + window pattern) the tile that holds it
+// simply runs its whole range and is launched first.  With more (strided patterns) the column
+// parts are split off: the COLUMN instance of the kernel packs the 64-key column groups four at
+// a time into virtual 256-key tiles, so that all 8 waves have live keys and a Q / dO tile is
+// used by 256 keys again, cuts their query range into chunks of LG_COL_CHUNK tiles that run as
+// separate workgroups, and adds float32 partial sums into the workspace with hardware atomics
+// (their order is not fixed, so the last bits of dk/dv of column keys can differ from run to
+// run).  The main instance then handles the window part of every tile and folds the partial
+// sums in before it rounds to bf16.  The table kernel lists the column groups once per call.
+constexpr int LG_COL_CHUNK = 64;  // query tiles (64 rows each) per column workgroup
+
+// col_of_group[c] = index of 64-key group c among the column groups, or -1; col_list = inverse.
+__global__ void dkdv_column_table_kernel(int* __restrict__ col_of_group, int* __restrict__ col_list,
+                                         LgMask m, int ngroups) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int n = 0;
+  for (int c = 0; c < ngroups; ++c) {
+    const bool is = lg_is_column_group(m, c, LG_BF16_BTK, LG_BF16_BTQ);
+    col_of_group[c] = is ? n : -1;
+    if (is) col_list[n++] = c;
+  }
+}
+
+__global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4) {
+  for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < n4; x += (size_t)gridDim.x * blockDim.x)
+    p[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ncol: column groups handled by the COLUMN instance (0: none are split off)
+template <int D, bool TOKEN, bool COLUMN>
 __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
-    int nkt, int total, int per_xcd) {
+    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
+    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -228,33 +261,65 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, lse*log2e | Delta (2 x 64 floats)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[VRES + 2 * STAGE];
 
-  // Launch order.  Key tile 0 of every (b, kv head) holds the sink keys, which every later
-  // query tile attends to: its workgroup runs ~N/64 steps instead of ~(window+256)/64.  Those
-  // nbh workgroups take the first block ids (dealt round-robin over the XCDs, so they start
-  // at once and spread evenly); the remaining (head, key tile) items follow in XCD-contiguous
-  // chunks so that neighbouring key tiles share their Q / dO rows in one XCD's L2.
-  // per_xcd counts the chunked items per XCD; total = nbh * nkt items overall.
-  const int nbh = total / nkt;
-  int bh, kt;
-  if ((int)blockIdx.x < nbh) {
-    bh = blockIdx.x;
-    kt = 0;
-  } else {
-    const int idx = blockIdx.x - nbh;
-    const int L = (idx % 8) * per_xcd + idx / 8;
-    if (nkt == 1 || L >= total - nbh) return;
-    bh = L / (nkt - 1);
-    kt = 1 + L % (nkt - 1);
-  }
-  const int b = bh / Hkv, hk = bh % Hkv;
   const int G = Hq / Hkv;
   const int N = m.N;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  // Work item.
+  //   main, no split-off columns: key tile 0 of every (b, kv head) holds the sink keys and runs
+  //     ~N/64 steps instead of ~(window+256)/64, so those workgroups take the first block ids
+  //     (dealt round-robin over the XCDs: they start at once, spread evenly); the other
+  //     (head, key tile) items follow in XCD-contiguous runs, so that neighbouring key tiles
+  //     share their Q / dO rows in one XCD's L2.
+  //   main, columns split off: all items in XCD-contiguous runs.
+  //   COLUMN: blockIdx.x = (((b x kv head) * G + query head of the group) * nvt + virtual tile)
+  //     * nchunk + chunk; chunks past the end of the range exit at once.
+  int bh, kt = 0, vt = 0, chunk = 0, gq = 0;
+  if (COLUMN) {
+    const int nvt = (ncol + 3) / 4;
+    int x = blockIdx.x;
+    chunk = x % nchunk;
+    x /= nchunk;
+    vt = x % nvt;
+    x /= nvt;
+    gq = x % G;
+    bh = x / G;
+  } else if (ncol > 0) {
+    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (L >= total) return;
+    bh = L / nkt;
+    kt = L % nkt;
+  } else {
+    const int nbh = total / nkt;
+    if ((int)blockIdx.x < nbh) {
+      bh = blockIdx.x;
+      kt = 0;
+    } else {
+      const int idx = blockIdx.x - nbh;
+      const int L = (idx % 8) * per_xcd + idx / 8;
+      if (nkt == 1 || L >= total - nbh) return;
+      bh = L / (nkt - 1);
+      kt = 1 + L % (nkt - 1);
+    }
+  }
+  const int b = bh / Hkv, hk = bh % Hkv;
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
   const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
-  const int j = k0 + wave * 32 + n;  // this lane's key
-  const int kw0 = k0 + __builtin_amdgcn_readfirstlane(wave) * 32;  // this wave's first key
+  // this wave's 32 keys: part of the key tile, or half of one of the virtual tile's column groups
+  int kw0 = k0 + wave_s * 32;
+  int col_gi = 0;        // COLUMN: index of this wave's column group
+  bool active = true;    // COLUMN: the virtual tile may have fewer than 4 groups
+  int r0_w = 0;          // COLUMN: first row of the wave's column part
+  if (COLUMN) {
+    col_gi = 4 * vt + (wave_s >> 1);
+    active = col_gi < ncol;
+    const int grp = col_list[min(col_gi, ncol - 1)];
+    kw0 = 64 * grp + 32 * (wave_s & 1);
+    const int t1 = min((64 * grp / TK) * TK + TK - 1, N - 1);
+    r0_w = (lg_qtile_window_hi(m, t1, TQ) + 1) * TQ;
+  }
+  const int j = kw0 + n;  // this lane's key
   const int jk = min(j, N - 1);
 
   bf16x8_t kf[DC];
@@ -269,10 +334,24 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) ak[db][r] = av[db][r] = 0.f;
-  int lo, hi;
-  lg_qtile_range(m, k0, k1, TQ, &lo, &hi);
+  // query tiles of this work item
+  int lo, hi, hq0 = hk * G, nheads = G;
+  if (COLUMN) {  // one chunk of the rows after the window part of the virtual tile's first group
+    const int grp0 = col_list[4 * vt];
+    const int t1 = min((64 * grp0 / TK) * TK + TK - 1, N - 1);
+    lo = lg_qtile_window_hi(m, t1, TQ) + 1 + chunk * LG_COL_CHUNK;
+    hi = min((N - 1) / TQ, lo + LG_COL_CHUNK - 1);
+    if (lo > hi) return;
+    hq0 += gq;
+    nheads = 1;
+  } else if (ncol > 0) {  // the window part; the column part is the COLUMN instance's
+    lo = k0 / TQ;
+    hi = lg_qtile_window_hi(m, k1, TQ);
+  } else {
+    lg_qtile_range(m, k0, k1, TQ, &lo, &hi);
+  }
   const int per_head = hi - lo + 1;
-  const int steps = per_head * G;
+  const int steps = per_head * nheads;
 
   Dma dma;
   dma.init(tid);
@@ -282,7 +361,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   // the workgroup's V rows, resident for the whole kernel
 #pragma unroll
   for (int x = 0; x < 4; ++x) {
-    const int r0 = k0 + 64 * x;
+    const int r0 = COLUMN ? 64 * col_list[min(4 * vt + x, ncol - 1)] : k0 + 64 * x;
     const int rc = min(r0, N - 1);  // a tile wholly past the end repeats the last row
     dma.issue(v + kbase + (size_t)rc * D, r0 < N ? N - r0 : 1, lds0 + x * T::BYTES);
   }
@@ -303,7 +382,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
   };
 
-  int hq_i = hk * G, u_i = lo;   // step being issued
+  int hq_i = hq0, u_i = lo;      // step being issued
   int u_c = lo;                  // query tile of the step being computed
   issue_step(hq_i, u_i, 0);
   for (int st = 0; st < steps; ++st) {
@@ -322,6 +401,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const int q1 = min(q0 + TQ - 1, N - 1);
     // this wave's 32 keys against the step's 64 queries: a wave with no live pair sits the step
     // out (most waves of the sink key tile do, once the queries are past its window)
+    if (COLUMN && (!active || q0 < r0_w)) continue;  // no group, or rows of its window part
     const int kind = lg_tile_kind(m, q0, q1, kw0, kw0 + 31);
     if (kind == LG_TILE_DEAD) continue;
     const bool full = kind == LG_TILE_FULL && q0 + TQ <= N;
@@ -406,6 +486,34 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     }
   }
 
+  // partial sums of the column parts: [b x kv head][column group][64 keys][D] float32, dk unscaled
+  if (COLUMN) {
+    if (active && j < N) {
+      const size_t prow = (((size_t)bh * ncol + col_gi) * 64 + (wave_s & 1) * 32 + n) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int d = db * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          unsafeAtomicAdd(part_dk + prow + d, ak[db][r]);  // hardware float add in L2
+          unsafeAtomicAdd(part_dv + prow + d, av[db][r]);
+        }
+    }
+    return;
+  }
+  const int cid = (ncol > 0 && kw0 < N) ? col_of_group[kw0 >> 6] : -1;
+  if (cid >= 0 && j < N) {
+    const size_t prow = (((size_t)bh * ncol + cid) * 64 + (wave_s & 1) * 32 + n) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const float4 pk = *reinterpret_cast<const float4*>(part_dk + prow + db * 32 + 8 * r4 + 4 * g);
+        const float4 pv = *reinterpret_cast<const float4*>(part_dv + prow + db * 32 + 8 * r4 + 4 * g);
+        ak[db][4 * r4 + 0] += pk.x; ak[db][4 * r4 + 1] += pk.y; ak[db][4 * r4 + 2] += pk.z; ak[db][4 * r4 + 3] += pk.w;
+        av[db][4 * r4 + 0] += pv.x; av[db][4 * r4 + 1] += pv.y; av[db][4 * r4 + 2] += pv.z; av[db][4 * r4 + 3] += pv.w;
+      }
+  }
   if (j < N) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -423,6 +531,46 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 }
 
 }  // namespace
+
+// Workspace of the bf16 backward after Delta: two int tables of nkt entries, then the float32
+// partial sums of the column tiles (dk, then dv).
+namespace {
+struct ColumnLayout {
+  int nkt, ngroups, ncol, nchunk;  // ncol = 0: no column parts are split off
+  size_t tab_off, pdk_off, pdv_off, end;
+};
+ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t delta_bytes) {
+  ColumnLayout c;
+  c.nkt = (sh.N + LG_BF16_BTK - 1) / LG_BF16_BTK;
+  c.ngroups = (sh.N + 63) / 64;
+  c.ncol = 0;
+  int first = -1;
+  for (int grp = 0; grp < c.ngroups; ++grp)
+    if (lg_is_column_group(m, grp, LG_BF16_BTK, LG_BF16_BTQ)) {
+      if (first < 0) first = grp;
+      ++c.ncol;
+    }
+  if (c.ncol < 2) c.ncol = 0;  // a lone group (the sink) stays with its key tile, launched first
+  c.nchunk = 0;
+  if (c.ncol > 0) {  // the first group has the longest column part
+    const int t0 = (first * 64 / LG_BF16_BTK) * LG_BF16_BTK;
+    const int t1 = (t0 + LG_BF16_BTK - 1 < sh.N - 1) ? t0 + LG_BF16_BTK - 1 : sh.N - 1;
+    const int far = (sh.N - 1) / LG_BF16_BTQ - lg_qtile_window_hi(m, t1, LG_BF16_BTQ);
+    c.nchunk = (far + LG_COL_CHUNK - 1) / LG_COL_CHUNK;
+  }
+  c.tab_off = delta_bytes;
+  const size_t tab = (((size_t)2 * c.ngroups * sizeof(int)) + 255) & ~(size_t)255;
+  const size_t part = (size_t)sh.B * sh.Hkv * c.ncol * 64 * sh.D * sizeof(float);
+  c.pdk_off = c.tab_off + (c.ncol > 0 ? tab : 0);
+  c.pdv_off = c.pdk_off + part;
+  c.end = c.pdv_off + part;
+  return c;
+}
+}  // namespace
+
+size_t lg_bwd_bf16_workspace_bytes(const LgShape& sh, const LgMask& m, size_t delta_bytes) {
+  return column_layout(sh, m, delta_bytes).end;
+}
 
 hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const void* out,
                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
@@ -460,22 +608,53 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (ev) (void)hipEventRecord(ev[2], s);
   }
   {
-    const int nkt = (sh.N + LG_BF16_BTK - 1) / LG_BF16_BTK;
+    const size_t delta_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
+    const ColumnLayout cl = column_layout(sh, m, delta_bytes);
+    const int nkt = cl.nkt;
     const long long tl = (long long)nkt * sh.Hkv * sh.B;
+    if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
     const int total = (int)tl, nbh = sh.Hkv * sh.B;
-    const int per_xcd = (total - nbh + 7) / 8;  // chunked items (all but key tile 0) per XCD
-    const dim3 grid(nbh + per_xcd * 8);
-#define LG_DKDV_LAUNCH(DD, TT)                                                                  \
-  dkdv_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,         \
-                                                (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt,   \
-                                                total, per_xcd)
-    if (sh.D == 64) {
-      if (token) LG_DKDV_LAUNCH(64, true);
-      else LG_DKDV_LAUNCH(64, false);
-    } else {
-      if (token) LG_DKDV_LAUNCH(128, true);
-      else LG_DKDV_LAUNCH(128, false);
+    const int per_xcd = (total + 7) / 8;
+    int* col_of_group = (int*)((char*)ws + cl.tab_off);
+    int* col_list = col_of_group + cl.ngroups;
+    float* pdk = (float*)((char*)ws + cl.pdk_off);
+    float* pdv = (float*)((char*)ws + cl.pdv_off);
+#define LG_DKDV_LAUNCH(DD, TT, CC, GRID)                                                                  \
+  dkdv_bf16_kernel<DD, TT, CC><<<GRID, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,               \
+                                                    (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,  \
+                                                    per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol,     \
+                                                    cl.nchunk)
+#define LG_DKDV_BOTH(CC, GRID)                          \
+  do {                                                  \
+    if (sh.D == 64) {                                   \
+      if (token) LG_DKDV_LAUNCH(64, true, CC, GRID);    \
+      else LG_DKDV_LAUNCH(64, false, CC, GRID);         \
+    } else {                                            \
+      if (token) LG_DKDV_LAUNCH(128, true, CC, GRID);   \
+      else LG_DKDV_LAUNCH(128, false, CC, GRID);        \
+    }                                                   \
+  } while (0)
+    if (cl.ncol > 0) {
+      // list the column groups, clear their partial sums, run the column parts
+      const long long ncolwg = (long long)((cl.ncol + 3) / 4) * cl.nchunk * sh.Hq * sh.B;
+      if (ncolwg > 0x7fffffffLL) return hipErrorInvalidValue;
+      dkdv_column_table_kernel<<<1, 64, 0, s>>>(col_of_group, col_list, m, cl.ngroups);
+      const size_t n4 = (cl.end - cl.pdk_off) / sizeof(float4);
+      fill_zero_kernel<<<dim3((unsigned)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048)), 256, 0, s>>>(
+          (float4*)pdk, n4);
+      const dim3 grid_col((unsigned)ncolwg);
+      LG_DKDV_BOTH(true, grid_col);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
     }
+    // main instance: all items in XCD-contiguous runs, or (no split-off columns) the sink tiles first
+    const int per_xcd_main = cl.ncol > 0 ? per_xcd : (total - nbh + 7) / 8;
+    const dim3 grid_main(cl.ncol > 0 ? per_xcd * 8 : nbh + per_xcd_main * 8);
+    {
+      const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
+      LG_DKDV_BOTH(false, grid_main);
+    }
+#undef LG_DKDV_BOTH
 #undef LG_DKDV_LAUNCH
     e = hipGetLastError();
     if (ev) (void)hipEventRecord(ev[3], s);

@@ -233,10 +233,10 @@ hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, long
                          : launch_delta_t<__hip_bfloat16>(dout, out, delta, rows, D, s);
 }
 
-size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask&, int) {
-  // Delta [B, Hq, N] float32, rounded up to 256 bytes
-  const size_t n = (size_t)sh.B * sh.Hq * sh.N * sizeof(float);
-  return (n + 255) & ~(size_t)255;
+size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype) {
+  // Delta [B, Hq, N] float32, rounded up to 256 bytes; the bf16 path adds its column-tile area
+  const size_t n = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
+  return dtype == LG_BF16 ? lg_bwd_bf16_workspace_bytes(sh, m, n) : n;
 }
 
 hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, const float* out,

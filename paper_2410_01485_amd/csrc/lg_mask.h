@@ -288,4 +288,32 @@ LG_HD long long lg_cache_slots(int n_max, const LgMask& m) {
   return (long long)m.sink + m.window + (m.stride > 0 ? (nb / m.stride) * m.b : 0);
 }
 
+// ---------------------------------------------------------------------------------
+// Column keys: sink tokens and the keys of strided block columns are seen by EVERY later
+// query, not only by the queries whose window reaches them.  The dk/dv pass treats the two
+// parts of a key tile's query range separately (window part: dense, ~window/Tq tiles; column
+// part: all later query tiles, but only for the few column keys).
+
+// Does [k0, k1] hold a column key?
+LG_HD bool lg_has_column_key(const LgMask& m, int k0, int k1) {
+  if (k0 < m.sink) return true;
+  return m.stride > 0 && lg_next_strided_block(m, lg_div_b(m, k0)) <= lg_div_b(m, k1);
+}
+
+// Last query tile (Tq rows) that the window of key k1 (<= N-1) reaches.
+LG_HD int lg_qtile_window_hi(const LgMask& m, int k1, int Tq) {
+  long long last = m.N - 1;
+  const long long w = ((long long)lg_div_b(m, k1) + m.wb) * m.b - 1;
+  if (w < last) last = w;
+  return (int)(last / Tq);
+}
+
+// Is the 64-key group c a column group: column keys AND query rows beyond the window part of
+// the Tk-key tile it belongs to?  (The window part of a tile is the same for all its keys.)
+LG_HD bool lg_is_column_group(const LgMask& m, int c, int Tk, int Tq) {
+  const int g0 = c * 64, g1 = (g0 + 63 < m.N - 1) ? g0 + 63 : m.N - 1;
+  const int t0 = (g0 / Tk) * Tk, t1 = (t0 + Tk - 1 < m.N - 1) ? t0 + Tk - 1 : m.N - 1;
+  return lg_has_column_key(m, g0, g1) && lg_qtile_window_hi(m, t1, Tq) < (m.N - 1) / Tq;
+}
+
 #endif  // LG_MASK_H_

@@ -83,6 +83,18 @@ def test_masked_keys_get_exactly_zero_gradient(dtype):
     assert np.abs(f32np(dq)[:, :, rows]).sum() > 0
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,sink,window,block,stride", [
+    # several column groups (sink + strided blocks), column parts longer than one chunk of 4096
+    # rows, GQA, ragged ends; a virtual tile with fewer than 4 groups; token-granular strided columns
+    (1, 4, 2, 9000, 128, 64, 128, 64, 4),
+    (2, 2, 2, 5003, 64, 16, 48, 16, 3),
+    (1, 2, 1, 4700, 128, 0, 64, 64, 16),
+    (1, 2, 2, 4500, 128, 2, 6, 1, 9),
+])
+def test_strided_columns_long_context(B, Hq, Hkv, N, D, sink, window, block, stride):
+    check_bwd(B, Hq, Hkv, N, D, sink, window, block, stride, dtype=torch.bfloat16, seed=41)
+
+
 def test_bwd_deterministic():
     q, k, v, g = lg_synth.prefill_inputs(1, 4, 2, 900, 128, 9, torch.bfloat16, with_dout=True)
     a = run_fwd_bwd(q, k, v, g, 64, 300)

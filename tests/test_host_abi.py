@@ -77,7 +77,8 @@ def test_decode_argument_errors():
 
     assert dec(q=None) == 1
     assert dec(N=0) == 2 and dec(window=0) == 2 and dec(Hq=3) == 2
-    assert dec(stride=4) == 3 and dec(block=4, sink=4, window=28) == 3 and dec(D=32) == 3
+    # a strided pattern needs the retained-block part of the cache: lg_sparse_attn_decode_cache
+    assert dec(stride=4) == 3 and dec(block=4, sink=4, window=28, stride=2) == 3 and dec(D=32) == 3
     assert dec(Hq=64, Hkv=2) == 3                                        # group larger than 16
     need = lg.decode_workspace_bytes(1, 1, 1, 100000, 128, 64, 4096, lg.LG_BF16)
     assert need > 0
