@@ -40,6 +40,19 @@ def live_pairs(N, sink, window):
     return sum(min(i + 1, window) + min(sink, max(0, i - window + 1)) for i in range(N))
 
 
+def block_pairs(N, sink, window, block, stride):
+    """Live (i, j) pairs of a block-granular pattern: per query block, the live key blocks below the
+    diagonal are whole, the diagonal block is causal."""
+    nb, sb, wb, tot = (N + block - 1) // block, sink // block, window // block, 0
+    for qb in range(nb):
+        rows = min(block, N - qb * block)
+        below = set(range(min(sb, qb))) | set(range(max(0, qb - wb + 1), qb))
+        if stride > 0:
+            below |= set(range(stride - 1, qb, stride))
+        tot += len(below) * rows * block + rows * (rows + 1) // 2
+    return tot
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +136,33 @@ def main():
                         "frac": round(fl_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)},
                 "bwd": {"ms": round(bwd_ms, 4), "tflops": round(fl_bwd / bwd_ms / 1e9, 1),
                         "frac": round(fl_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)}}
+    # the paper's own block-granular settings (Section 4.1) on the same tensors, 3 launches each:
+    # attention sink (1 sink block + 32 local blocks) and sink + local + every 64th block
+    paper = []
+    for name, (ps, pw, pb, pst) in (("attn_sink b64: sink 64, window 2048", (64, 2048, 64, 0)),
+                                    ("block_sparse b64: sink 64, window 2048, stride 64", (64, 2048, 64, 64))):
+        pws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, ps, pw, pb, pst, lg.LG_BF16),
+                          dtype=torch.uint8, device=dev)
+        pp = block_pairs(N, ps, pw, pb, pst) * H * B
+        lg.lg_sparse_attn_fwd(q, k, v, out, lse, ps, pw, pb, pst)
+        lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, pws, ps, pw, pb, pst)
+        torch.cuda.synchronize()
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        f_ms = b_ms = 0.0
+        for _ in range(3):
+            e0.record()
+            lg.lg_sparse_attn_fwd(q, k, v, out, lse, ps, pw, pb, pst)
+            e1.record()
+            lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, pws, ps, pw, pb, pst)
+            e2.record()
+            torch.cuda.synchronize()
+            f_ms += e0.elapsed_time(e1) / 3
+            b_ms += e1.elapsed_time(e2) / 3
+        paper.append({"pattern": name, "live_pairs_per_head": pp // (H * B), "fwd_ms": round(f_ms, 3),
+                      "bwd_ms": round(b_ms, 3),
+                      "tflops": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12, 1),
+                      "frac": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
+        del pws
     del q, k, v, g, out, lse, dq, dk, dv, ws
     torch.cuda.empty_cache()
 
@@ -217,7 +257,7 @@ def main():
                    "wall_ms_per_step": round(wall_ms, 3),
                    "ms_per_step_median": round(per_step[len(per_step) // 2], 3),
                    "ms_per_step_min": round(per_step[0], 3)},
-        "roofline": roofline, "cpu_baseline": cpu, "decode": decode,
+        "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "paper_block_settings": paper,
     }))
 
 

@@ -135,3 +135,35 @@ def test_config3_full_size_sampled():
         assert_close(f32np(dk[0, h, keys[0]:keys[1]]), w["dk"][0, 0, keys[0]:keys[1]], tol, rel, "cfg3 dk h%d" % h)
         assert_close(f32np(dv[0, h, keys[0]:keys[1]]), w["dv"][0, 0, keys[0]:keys[1]], tol, rel, "cfg3 dv h%d" % h)
         assert_close(f32np(out[0, h, rows[0]:rows[1]]), w["out"][0, 0, rows[0]:rows[1]], tol, rel, "cfg3 out h%d" % h)
+
+
+def test_paper_block_settings_full_size_sampled():
+    """Section 4.1 settings combined at the training length: 64-token blocks, 1 sink block, 32 local blocks
+    and every 64th block as a strided column; B1, 32 heads, N=131072, D=128.  The oracle recomputes sampled
+    query rows (dq) and sampled keys (dk, dv): sink keys, keys of a strided column (seen by every later row,
+    accumulated over many workgroups), window-only keys, and the ragged end."""
+    B, H, N, D, sink, window, block, stride = 1, 32, 131072, 128, 64, 2048, 64, 64
+    q, k, v, g = lg_synth.prefill_inputs(B, H, H, N, D, 20241009, torch.bfloat16, with_dout=True, device=DEV)
+    out = torch.empty_like(q)
+    lse = torch.empty(B, H, N, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window, block, stride)
+    ws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, sink, window, block, stride, lg.LG_BF16),
+                     dtype=torch.uint8, device=DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window, block, stride)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    tol, rel = TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16]
+    col = 63 * 64  # first strided column block
+    for h, rows, keys in ((0, (0, 40), (20, 60)),                       # sink keys
+                          (7, (70001, 70041), (col + 10, col + 50)),    # a strided column
+                          (19, (100000, 100040), (90010, 90050)),       # window-only keys
+                          (31, (N - 40, N), (N - 40, N))):              # the end of the sequence
+        print("head", h, "rows", rows, "keys", keys, flush=True)
+        a = [f32np(x[:, h:h + 1]) for x in (q, k, v, g)]
+        w = O.bwd(*a, sink, window, block, stride, rows=rows, keys=keys)
+        assert_close(f32np(dq[0, h, rows[0]:rows[1]]), w["dq"][0, 0, rows[0]:rows[1]], tol, rel, "paper dq h%d" % h)
+        assert_close(f32np(dk[0, h, keys[0]:keys[1]]), w["dk"][0, 0, keys[0]:keys[1]], tol, rel, "paper dk h%d" % h)
+        assert_close(f32np(dv[0, h, keys[0]:keys[1]]), w["dv"][0, 0, keys[0]:keys[1]], tol, rel, "paper dv h%d" % h)
+        assert_close(f32np(out[0, h, rows[0]:rows[1]]), w["out"][0, 0, rows[0]:rows[1]], tol, rel, "paper out h%d" % h)
