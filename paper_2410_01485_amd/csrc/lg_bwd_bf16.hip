@@ -62,10 +62,14 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 
   const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (L >= total) return;
-  const int bh = L / nqt;
-  const int qt = nqt - 1 - (L % nqt);
-  const int b = bh / Hq, hq = bh % Hq;
-  const int hk = hq / (Hq / Hkv);
+  // logical order: (b, kv head) slowest, then query tile (longest rows first), then the query
+  // heads of the GQA group: the G workgroups that walk the same K/V tiles run side by side
+  const int G = Hq / Hkv;
+  const int gq = L % G, rest = L / G;
+  const int qt = nqt - 1 - (rest % nqt);
+  const int bhk = rest / nqt;
+  const int b = bhk / Hkv, hk = bhk % Hkv;
+  const int hq = hk * G + gq;
   const int N = m.N;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
