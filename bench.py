@@ -163,6 +163,27 @@ def main():
                       "tflops": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12, 1),
                       "frac": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
         del pws
+    # full causal attention through the same kernels (window >= N), one launch after a warm-up: the
+    # cost of a full-attention layer at this length, and what a 12 full + 20 sparse layer stack
+    # (the paper's hybrid) saves on attention alone
+    fws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, 0, N, 1, 0, lg.LG_BF16), dtype=torch.uint8, device=dev)
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
+    torch.cuda.synchronize()
+    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    e0.record()
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
+    e1.record()
+    lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, fws, 0, N)
+    e2.record()
+    torch.cuda.synchronize()
+    cf, cb = e0.elapsed_time(e1), e1.elapsed_time(e2)
+    cpairs = N * (N + 1) // 2 * H * B
+    full = {"workload": "full causal attention, same shape (window = N)", "fwd_ms": round(cf, 2),
+            "bwd_ms": round(cb, 2), "tflops": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12, 1),
+            "attention_speedup_12_full_20_sparse_vs_32_full": {
+                "train": round(32 * (cf + cb) / (12 * (cf + cb) + 20 * step_ms), 2),
+                "prefill": round(32 * cf / (12 * cf + 20 * fwd_ms), 2)}}
+    del fws
     del q, k, v, g, out, lse, dq, dk, dv, ws
     torch.cuda.empty_cache()
 
@@ -258,6 +279,7 @@ def main():
                    "ms_per_step_median": round(per_step[len(per_step) // 2], 3),
                    "ms_per_step_min": round(per_step[0], 3)},
         "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "paper_block_settings": paper,
+        "full_causal": full,
     }))
 
 
