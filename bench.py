@@ -28,10 +28,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # scaled by what the same counter reads for a copy kernel of known size.  Counter runs are
 # separate from timed runs, so these are constants here, not measured by this script.
 MEASURED_HBM_BYTES = {
-    "fwd_bf16_kernel": (17.60e9, 1.09e9),
-    "dq_bf16_kernel": (19.84e9, 1.07e9),
-    "dkdv_bf16_kernel": (10.69e9, 2.22e9),
-    "decode_kernel": (1.09e9, 0.15e6),
+    "fwd_bf16_kernel": (17.51e9, 1.090e9),
+    "dq_bf16_kernel": (20.34e9, 1.070e9),
+    "dkdv_bf16_kernel": (11.09e9, 2.250e9),
+    "decode_kernel": (1.09e9, 0.000e9),
 }
 
 
@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline workloads (training step, decode): what the kernel-trace profile runs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every (batch, head) is independent, so more GPUs "
@@ -139,8 +141,9 @@ def main():
     # the paper's own block-granular settings (Section 4.1) on the same tensors, 3 launches each:
     # attention sink (1 sink block + 32 local blocks) and sink + local + every 64th block
     paper = []
-    for name, (ps, pw, pb, pst) in (("attn_sink b64: sink 64, window 2048", (64, 2048, 64, 0)),
-                                    ("block_sparse b64: sink 64, window 2048, stride 64", (64, 2048, 64, 64))):
+    for name, (ps, pw, pb, pst) in (() if args.no_extras else
+                                    (("attn_sink b64: sink 64, window 2048", (64, 2048, 64, 0)),
+                                     ("block_sparse b64: sink 64, window 2048, stride 64", (64, 2048, 64, 64)))):
         pws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, ps, pw, pb, pst, lg.LG_BF16),
                           dtype=torch.uint8, device=dev)
         pp = block_pairs(N, ps, pw, pb, pst) * H * B
@@ -166,24 +169,27 @@ def main():
     # full causal attention through the same kernels (window >= N), one launch after a warm-up: the
     # cost of a full-attention layer at this length, and what a 12 full + 20 sparse layer stack
     # (the paper's hybrid) saves on attention alone
-    fws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, 0, N, 1, 0, lg.LG_BF16), dtype=torch.uint8, device=dev)
-    lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
-    torch.cuda.synchronize()
-    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-    e0.record()
-    lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
-    e1.record()
-    lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, fws, 0, N)
-    e2.record()
-    torch.cuda.synchronize()
-    cf, cb = e0.elapsed_time(e1), e1.elapsed_time(e2)
-    cpairs = N * (N + 1) // 2 * H * B
-    full = {"workload": "full causal attention, same shape (window = N)", "fwd_ms": round(cf, 2),
-            "bwd_ms": round(cb, 2), "tflops": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12, 1),
-            "attention_speedup_12_full_20_sparse_vs_32_full": {
-                "train": round(32 * (cf + cb) / (12 * (cf + cb) + 20 * step_ms), 2),
-                "prefill": round(32 * cf / (12 * cf + 20 * fwd_ms), 2)}}
-    del fws
+    full = None
+    if not args.no_extras:
+        fws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, 0, N, 1, 0, lg.LG_BF16), dtype=torch.uint8,
+                          device=dev)
+        lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
+        torch.cuda.synchronize()
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record()
+        lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
+        e1.record()
+        lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, fws, 0, N)
+        e2.record()
+        torch.cuda.synchronize()
+        cf, cb = e0.elapsed_time(e1), e1.elapsed_time(e2)
+        cpairs = N * (N + 1) // 2 * H * B
+        full = {"workload": "full causal attention, same shape (window = N)", "fwd_ms": round(cf, 2),
+                "bwd_ms": round(cb, 2), "tflops": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12, 1),
+                "attention_speedup_12_full_20_sparse_vs_32_full": {
+                    "train": round(32 * (cf + cb) / (12 * (cf + cb) + 20 * step_ms), 2),
+                    "prefill": round(32 * cf / (12 * cf + 20 * fwd_ms), 2)}}
+        del fws
     del q, k, v, g, out, lse, dq, dk, dv, ws
     torch.cuda.empty_cache()
 
@@ -224,7 +230,7 @@ def main():
                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4),
                            "traffic": sum(MEASURED_HBM_BYTES["decode_kernel"])}}
 
-    # the block-sparse + sink + window pattern of Section 4.1 over the same cache tensors:
+    # (extras) the block-sparse + sink + window pattern of Section 4.1 over the same cache tensors:
     # 64-token blocks, 1 sink block, 32 local blocks, one retained block per 64 (4160 slots too)
     pb, ps, pwin, pstr = 64, 64, 2048, 64
     assert lg.lg_kv_cache_slots(dN, ps, pwin, pb, pstr) == C
