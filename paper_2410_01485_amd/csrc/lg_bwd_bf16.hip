@@ -115,12 +115,18 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
     dma.issue(vh + off, N - t * TK, lds0 + stage * STAGE + T::BYTES);
   };
 
-  int t = lg_qsched_next(m, qs, -1);
+  // token-granular patterns walk the window run rotated (L2 sharing between neighbours)
+  const LgQWalk qw = lg_qwalk_init(qs);
+  auto next_tile = [&](int prev) -> int {
+    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    return lg_qsched_next(m, qs, prev);
+  };
+  int t = next_tile(-1);
   int t_issue = t;
   int ahead = 0;
   for (; ahead < STAGES - 1 && t_issue >= 0; ++ahead) {
     issue(t_issue, ahead);
-    t_issue = lg_qsched_next(m, qs, t_issue);
+    t_issue = next_tile(t_issue);
   }
   int stage = 0;
   while (t >= 0) {
@@ -130,7 +136,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
     __syncthreads();  // tile t landed for everyone; everyone is done with tile t-1
     if (t_issue >= 0) {
       issue(t_issue, (stage + STAGES - 1) % STAGES);
-      t_issue = lg_qsched_next(m, qs, t_issue);
+      t_issue = next_tile(t_issue);
       ++ahead;
     }
     const int k0 = t * TK;
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
       }
     }
     --ahead;
-    t = lg_qsched_next(m, qs, t);
+    t = next_tile(t);
     stage = (stage + 1) % STAGES;
   }
 
@@ -386,16 +392,23 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
   };
 
-  int hq_i = hq0, u_i = lo;      // step being issued
-  int u_c = lo;                  // query tile of the step being computed
+  // The query tiles [lo, hi] of a head are walked rotated: at step x the tile congruent to x
+  // modulo the range length.  Neighbouring key tiles, whose ranges overlap almost completely and
+  // which run side by side, then read the same Q / dO tile at the same time and share it in L2.
+  const int u0 = lo + (per_head - lo % per_head) % per_head;
+  int hq_i = hq0, u_i = u0;      // step being issued
+  int u_c = u0;                  // query tile of the step being computed
+  int left_i = per_head;         // steps of the head being issued that are not issued yet
   issue_step(hq_i, u_i, 0);
   for (int st = 0; st < steps; ++st) {
     const int buf = st & 1;
     LG_WAIT_VMCNT(0);
     __syncthreads();  // step st landed for everyone; everyone is done with step st-1
     if (st + 1 < steps) {
-      if (++u_i > hi) {
-        u_i = lo;
+      u_i = (u_i == hi) ? lo : u_i + 1;
+      if (--left_i == 0) {  // next query head of the group: same walk again
+        left_i = per_head;
+        u_i = u0;
         ++hq_i;
       }
       issue_step(hq_i, u_i, buf ^ 1);

@@ -113,12 +113,18 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
 
   // ring: tiles are issued up to 3 ahead of the one being computed
   const LgQSched qs = lg_qsched_init(m, q0, q1);
-  int t = lg_qsched_next(m, qs, -1);  // tile to compute next
+  // token-granular patterns walk the window run rotated (L2 sharing between neighbours)
+  const LgQWalk qw = lg_qwalk_init(qs);
+  auto next_tile = [&](int prev) -> int {
+    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    return lg_qsched_next(m, qs, prev);
+  };
+  int t = next_tile(-1);  // tile to compute next
   int t_issue = t;                           // tile to issue next
   int ahead = 0;                             // tiles issued and not yet computed
   for (; ahead < STAGES - 1 && t_issue >= 0; ++ahead) {
     issue(t_issue, ahead);
-    t_issue = lg_qsched_next(m, qs, t_issue);
+    t_issue = next_tile(t_issue);
   }
 
   int stage = 0;  // ring position of tile t
@@ -130,7 +136,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
     __syncthreads();  // everyone's loads of tile t landed; everyone is done with tile t-1
     if (t_issue >= 0) {
       issue(t_issue, (stage + STAGES - 1) % STAGES);  // into the stage tile t-1 just left
-      t_issue = lg_qsched_next(m, qs, t_issue);
+      t_issue = next_tile(t_issue);
       ++ahead;
     }
 
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
     }  // kind != dead
 
     --ahead;
-    t = lg_qsched_next(m, qs, t);
+    t = next_tile(t);
     stage = (stage + 1) % STAGES;
   }
 

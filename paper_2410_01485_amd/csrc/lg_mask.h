@@ -187,6 +187,38 @@ LG_HD bool lg_qsched_full(const LgMask& m, const LgQSched& s, int t) {
   return kb == lg_div_b(m, hi) && lg_strided(m, kb);
 }
 
+// Walk order for patterns without strided columns (the live key tiles of a query tile are then
+// the sink tiles plus ONE contiguous run [tws, tmax]).  The online softmax takes tiles in any
+// order, so the run is walked rotated: at step x every query tile is at the key tile of its run
+// that is congruent to x modulo the run length.  Query tiles that are computed side by side
+// (neighbours, whose runs overlap almost completely) therefore read the SAME key tile at the
+// same time and share it in L2, instead of trailing each other by a few tiles.
+struct LgQWalk {
+  int nsink;   // sink tiles [0, nsink) come first
+  int tws;     // first tile of the window run
+  int tmax;    // last tile of the window run
+  int tstart;  // where the rotated walk of the run starts (-1: the run is empty)
+};
+
+LG_HD LgQWalk lg_qwalk_init(const LgQSched& s) {
+  LgQWalk w;
+  w.tmax = s.tmax;
+  w.nsink = s.tS < s.tmax + 1 ? s.tS : s.tmax + 1;
+  w.tws = s.tS > s.tW ? s.tS : s.tW;
+  const int len = w.tmax - w.tws + 1;
+  w.tstart = len > 0 ? w.tws + (len - w.tws % len) % len : -1;
+  return w;
+}
+
+LG_HD int lg_qwalk_first(const LgQWalk& w) { return w.nsink > 0 ? 0 : w.tstart; }
+
+// Tile after t in the walk, or -1.
+LG_HD int lg_qwalk_next(const LgQWalk& w, int t) {
+  if (t < w.nsink) return t + 1 < w.nsink ? t + 1 : w.tstart;
+  const int n = t == w.tmax ? w.tws : t + 1;
+  return n == w.tstart ? -1 : n;
+}
+
 // Live query tiles (tile = rows [u*Tq, u*Tq+Tq-1]) of the keys [k0, k1] (k1 <= N-1):
 // always one contiguous range [*lo, *hi].
 LG_HD void lg_qtile_range(const LgMask& m, int k0, int k1, int Tq, int* lo, int* hi) {
