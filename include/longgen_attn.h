@@ -217,7 +217,9 @@ int lg_debug_decode_segments(int N, int sink, int window, int block, int stride,
  * capacity of col_idx/kind in entries and row_cap that of row_ptr; *needed
  * always receives the number of live tiles and *rows the number of rows, and
  * nothing is written past a capacity (call once with cap = 0 to size).
- * Runs the same source the kernels compile (no GPU needed).
+ * Runs the same source the kernels compile (no GPU needed).  The lists are in increasing
+ * tile order; the kernels visit the same tiles, some of them in a rotated order (the result of
+ * the online softmax and of the gradient sums does not depend on the order).
  */
 int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dtype, int transposed,
                       int* tq, int* tk, int32_t* row_ptr, size_t row_cap,
