@@ -197,6 +197,37 @@ int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* 
                                 int sink, int window, int block, int stride, int cache_slots,
                                 int dtype, float scale, void* hip_stream);
 /*
+ * Serving-style layout (the paper's inference section measures inside a paged-cache serving
+ * engine): a paged cache shared by sequences of different lengths.
+ *   k_pages, v_pages : [num_pages, Hkv, page_size, D] device; page_size a power of two, 16..4096
+ *   page_table       : [B, pages_per_seq] int32 device; entry x of sequence b names the page that
+ *                      holds its cache slots [x*page_size, (x+1)*page_size); the slot layout of a
+ *                      sequence is the one of lg_kv_ring_append
+ *   seq_lens         : [B] int32 device, context length of each sequence (the query is its last
+ *                      token); values outside [1, n_max] are clamped
+ *   positions        : [B] int32 device, position of the first of the T new tokens per sequence
+ * n_max bounds the context lengths: pages_per_seq * page_size >= lg_kv_cache_slots(n_max, ...)
+ * is required, and the workspace is sized for it.  Page numbers are not checked on the device:
+ * every entry a sequence can reach must be < num_pages.
+ * lg_kv_paged_append stores k_new, v_new [B, Hkv, T, D]; a strided-block copy whose slot lies
+ * beyond pages_per_seq pages is dropped.
+ */
+size_t lg_sparse_attn_decode_paged_workspace_bytes(int B, int Hq, int Hkv, int n_max, int D,
+                                                   int sink, int window, int block, int stride, int dtype);
+int lg_sparse_attn_decode_paged(const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* page_table, const int32_t* seq_lens, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes,
+                                int B, int Hq, int Hkv, int n_max, int D,
+                                int sink, int window, int block, int stride,
+                                int page_size, int pages_per_seq, int num_pages,
+                                int dtype, float scale, void* hip_stream);
+int lg_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                       const int32_t* page_table, const int32_t* positions,
+                       int B, int Hkv, int D, int T, int n_max,
+                       int sink, int window, int block, int stride,
+                       int page_size, int pages_per_seq, int num_pages, int dtype, void* hip_stream);
+
+/*
  * Host-only: the runs of consecutive cache slots a decode step at context length N reads
  * (at most 4; start/len are HOST arrays of 4 entries; *nseg receives the count).  Runs the
  * same source the decode launch uses (no GPU needed).

@@ -55,6 +55,12 @@ def lib():
         L.lg_sparse_attn_decode_cache_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode_cache.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 10 + [_i, _f, _vp]
         L.lg_sparse_attn_decode_cache.restype = _i
+        L.lg_sparse_attn_decode_paged_workspace_bytes.argtypes = [_i] * 10
+        L.lg_sparse_attn_decode_paged_workspace_bytes.restype = _sz
+        L.lg_sparse_attn_decode_paged.argtypes = [_vp] * 7 + [_vp, _sz] + [_i] * 12 + [_i, _f, _vp]
+        L.lg_sparse_attn_decode_paged.restype = _i
+        L.lg_kv_paged_append.argtypes = [_vp] * 6 + [_i] * 12 + [_i, _vp]
+        L.lg_kv_paged_append.restype = _i
         L.lg_debug_decode_segments.argtypes = [_i] * 5 + [ctypes.POINTER(_i), _vp, _vp]
         L.lg_debug_decode_segments.restype = _i
         L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
@@ -203,6 +209,52 @@ def lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, workspace, N, sin
                                            scale, _stream(q))
     if st != 0:
         raise LgError(st, "lg_sparse_attn_decode_cache")
+
+
+def decode_paged_workspace_bytes(B, Hq, Hkv, n_max, D, sink, window, block, stride, dtype):
+    return int(lib().lg_sparse_attn_decode_paged_workspace_bytes(B, Hq, Hkv, n_max, D, sink, window, block, stride,
+                                                                 dtype))
+
+
+def _check_i32(t, *shape):
+    import torch
+    if t.dtype != torch.int32:
+        raise TypeError("expected an int32 tensor")
+    _check(t, *shape)
+
+
+def lg_sparse_attn_decode_paged(q, k_pages, v_pages, page_table, seq_lens, out, lse, workspace, n_max, sink, window,
+                                block=1, stride=0, scale=0.0):
+    """Decode over a paged cache: k_pages, v_pages [pages, Hkv, page_size, D]; page_table [B, pages_per_seq] and
+    seq_lens [B] int32 on the device."""
+    B, Hq, D = q.shape
+    num_pages, Hkv, page_size = k_pages.shape[0], k_pages.shape[1], k_pages.shape[2]
+    _check(k_pages, num_pages, Hkv, page_size, D), _check(v_pages, num_pages, Hkv, page_size, D), _check(out, B, Hq, D)
+    _check_i32(page_table, B, page_table.shape[1]), _check_i32(seq_lens, B)
+    if lse is not None:
+        _check(lse, B, Hq)
+    st = lib().lg_sparse_attn_decode_paged(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(seq_lens),
+                                           _ptr(out), _ptr(lse), _ptr(workspace),
+                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                           B, Hq, Hkv, n_max, D, sink, window, block, stride, page_size,
+                                           page_table.shape[1], num_pages, _dtype_code(q), scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_decode_paged")
+
+
+def lg_kv_paged_append(k_new, v_new, k_pages, v_pages, page_table, positions, n_max, sink, window, block=1,
+                       stride=0):
+    """Store k_new, v_new [B,Hkv,T,D] (sequence b: positions[b] .. +T-1) into the paged caches in place."""
+    B, Hkv, T, D = k_new.shape
+    num_pages, page_size = k_pages.shape[0], k_pages.shape[2]
+    _check(v_new, B, Hkv, T, D), _check(k_new, B, Hkv, T, D)
+    _check(k_pages, num_pages, Hkv, page_size, D), _check(v_pages, num_pages, Hkv, page_size, D)
+    _check_i32(page_table, B, page_table.shape[1]), _check_i32(positions, B)
+    st = lib().lg_kv_paged_append(_ptr(k_new), _ptr(v_new), _ptr(k_pages), _ptr(v_pages), _ptr(page_table),
+                                  _ptr(positions), B, Hkv, D, T, n_max, sink, window, block, stride, page_size,
+                                  page_table.shape[1], num_pages, _dtype_code(k_new), _stream(k_new))
+    if st != 0:
+        raise LgError(st, "lg_kv_paged_append")
 
 
 def lg_debug_decode_segments(N, sink, window, block=1, stride=0):

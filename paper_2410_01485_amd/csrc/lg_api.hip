@@ -215,6 +215,75 @@ int lg_sparse_attn_decode(const void* q, const void* k_cache, const void* v_cach
                                      D, sink, window, block, stride, sink + window, dtype, scale, hip_stream);
 }
 
+static int check_paged(int n_max, int sink, int window, int block, int stride, int page_size,
+                       int pages_per_seq, int num_pages, int* page_shift) {
+  if (page_size < 16 || page_size > 4096 || (page_size & (page_size - 1)) != 0) return LG_ERR_INVALID_ARG;
+  if (pages_per_seq < 1 || num_pages < 1) return LG_ERR_INVALID_ARG;
+  const size_t need = lg_kv_cache_slots(n_max, sink, window, block, stride);
+  if (need == 0 || (size_t)pages_per_seq * (size_t)page_size < need) return LG_ERR_INVALID_ARG;
+  int sh = 0;
+  while ((1 << sh) < page_size) ++sh;
+  *page_shift = sh;
+  return LG_OK;
+}
+
+size_t lg_sparse_attn_decode_paged_workspace_bytes(int B, int Hq, int Hkv, int n_max, int D,
+                                                   int sink, int window, int block, int stride, int dtype) {
+  return lg_sparse_attn_decode_cache_workspace_bytes(B, Hq, Hkv, n_max, D, sink, window, block, stride, dtype);
+}
+
+int lg_sparse_attn_decode_paged(const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* page_table, const int32_t* seq_lens, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes,
+                                int B, int Hq, int Hkv, int n_max, int D,
+                                int sink, int window, int block, int stride,
+                                int page_size, int pages_per_seq, int num_pages,
+                                int dtype, float scale, void* hip_stream) {
+  if (!q || !k_pages || !v_pages || !page_table || !seq_lens || !out) return LG_ERR_NULL;
+  int st = check_decode(B, Hq, Hkv, n_max, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  int page_shift = 0;
+  st = check_paged(n_max, sink, window, block, stride, page_size, pages_per_seq, num_pages, &page_shift);
+  if (st != LG_OK) return st;
+  if ((double)num_pages * Hkv * (double)page_size * D > 1099511627776.0) return LG_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out) || !aligned16(lse) ||
+      !aligned16(workspace) || ((uintptr_t)page_table & 3) || ((uintptr_t)seq_lens & 3))
+    return LG_ERR_INVALID_ARG;
+  const LgMask cm = lg_make_cache_mask(n_max, sink, window, block, stride);
+  const LgDecSegs g = lg_decode_segments(cm);  // the longest context: most keys
+  const size_t need = lg_decode_workspace_bytes(B, Hq, Hkv, D, g.pre[g.n]);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LG_ERR_WORKSPACE;
+  const LgShape sh = make_shape(B, Hq, Hkv, n_max, D, scale);
+  hipError_t e = lg_launch_decode(q, k_pages, v_pages, out, lse, workspace, B, Hq, Hkv, 0, g, D, dtype, sh.scale,
+                                  static_cast<hipStream_t>(hip_stream), page_table, seq_lens, pages_per_seq,
+                                  page_shift, n_max, &cm);
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+int lg_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                       const int32_t* page_table, const int32_t* positions,
+                       int B, int Hkv, int D, int T, int n_max,
+                       int sink, int window, int block, int stride,
+                       int page_size, int pages_per_seq, int num_pages, int dtype, void* hip_stream) {
+  if (!k_new || !v_new || !k_pages || !v_pages || !page_table || !positions) return LG_ERR_NULL;
+  if (T < 1 || T > n_max) return LG_ERR_INVALID_ARG;
+  int st = check_common(B, Hkv, Hkv, n_max, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  if ((double)sink + (double)window > 1073741824.0) return LG_ERR_INVALID_ARG;
+  int page_shift = 0;
+  st = check_paged(n_max, sink, window, block, stride, page_size, pages_per_seq, num_pages, &page_shift);
+  if (st != LG_OK) return st;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pages) || !aligned16(v_pages) ||
+      ((uintptr_t)page_table & 3) || ((uintptr_t)positions & 3))
+    return LG_ERR_INVALID_ARG;
+  const LgMask m = lg_make_cache_mask(n_max, sink, window, block, stride);
+  const int row_bytes = D * (dtype == LG_F32 ? 4 : 2);
+  hipError_t e = lg_launch_kv_paged_append(k_new, v_new, k_pages, v_pages, page_table, positions, B, Hkv,
+                                           row_bytes, T, pages_per_seq, page_shift, m,
+                                           static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
 int lg_debug_decode_segments(int N, int sink, int window, int block, int stride,
                              int* nseg, int32_t* start, int32_t* len) {
   if (!nseg || !start || !len) return LG_ERR_NULL;

@@ -14,7 +14,9 @@
 // The keys of a step are up to four runs of consecutive slots (LgDecSegs: sink tokens,
 // live part of the rolling window, retained strided blocks); the kernel walks their
 // concatenation.  The common case, one run starting at slot 0, has its own instance
-// without the index translation.
+// without the index translation.  A third instance serves paged caches with per-sequence
+// context lengths: the runs are computed per sequence on the device and a slot goes through
+// the sequence's page table.
 //
 // lg_kv_append_kernel stores new tokens into the cache rows by the same layout rule.
 #include <hip/hip_bf16.h>
@@ -83,14 +85,24 @@ __device__ __forceinline__ void store_out(__hip_bfloat16* p, float x) { *p = __f
 
 // Partial record in the workspace, per (b, hq, split): D accumulators, max, sum
 // (max and running values are in the log2 domain: score * scale * log2(e)).
-template <typename T, int D, int GT, bool SEGS>
+// What a paged launch adds to the arguments.
+struct LgPaged {
+  const int* page_table;  // [B, pages_per_seq]
+  const int* seq_lens;    // [B]
+  int pages_per_seq, page_shift, n_max;
+  LgMask cm;              // cache geometry (lg_make_cache_mask), N filled in per sequence
+};
+
+enum { LG_DEC_PLAIN = 0, LG_DEC_SEGS = 1, LG_DEC_PAGED = 2 };
+
+template <typename T, int D, int GT, int MODE>
 __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict__ q,
                                                             const T* __restrict__ kc,
                                                             const T* __restrict__ vc,
                                                             T* __restrict__ out, float* __restrict__ lse,
                                                             float* __restrict__ ws, int Hq, int Hkv,
                                                             int C, int valid, int chunk, int splits,
-                                                            float scale_log2e, LgDecSegs segs) {
+                                                            float scale_log2e, LgDecSegs segs, LgPaged pg) {
   constexpr int E = 16 / sizeof(T);      // elements per 16-byte lane load
   constexpr int LPR = D / E;             // lanes per key row
   constexpr int KPW = 64 / LPR;          // key rows per wave per load
@@ -106,6 +118,13 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = wave * KPW + lane / LPR;
   const int dl = (lane % LPR) * E;  // first head-dim element of this lane
+  if (MODE == LG_DEC_PAGED) {  // this sequence's own context length, key runs and share of the keys
+    LgMask cm = pg.cm;
+    cm.N = min(max(pg.seq_lens[b], 1), pg.n_max);
+    segs = lg_decode_segments(cm);
+    valid = segs.pre[segs.n];
+    chunk = (valid + splits - 1) / splits;
+  }
   const int s0 = split * chunk;
   const int s1 = min(valid, s0 + chunk);
 
@@ -123,8 +142,8 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
     }
   }
 
-  const T* kbase = kc + ((size_t)b * Hkv + hk) * C * D + dl;
-  const T* vbase = vc + ((size_t)b * Hkv + hk) * C * D + dl;
+  const T* kbase = kc + (MODE == LG_DEC_PAGED ? 0 : ((size_t)b * Hkv + hk) * C * D) + dl;
+  const T* vbase = vc + (MODE == LG_DEC_PAGED ? 0 : ((size_t)b * Hkv + hk) * C * D) + dl;
   for (int base = s0; base < s1; base += GROUPS * U) {
     float kf[U][E], vf[U][E];
     bool ok[U];
@@ -133,14 +152,18 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
       const int key = base + u * GROUPS + grp;  // index into the concatenated runs
       ok[u] = key < s1;
       int slot = ok[u] ? key : s1 - 1;
-      if (SEGS) {
+      if (MODE != LG_DEC_PLAIN) {
         int shift = segs.start[0];
         if (slot >= segs.pre[1]) shift = segs.start[1] - segs.pre[1];
         if (slot >= segs.pre[2]) shift = segs.start[2] - segs.pre[2];
         if (slot >= segs.pre[3]) shift = segs.start[3] - segs.pre[3];
         slot += shift;
       }
-      const size_t off = (size_t)slot * D;
+      size_t off = (size_t)slot * D;
+      if (MODE == LG_DEC_PAGED) {
+        const int page = pg.page_table[(size_t)b * pg.pages_per_seq + (slot >> pg.page_shift)];
+        off = ((((size_t)page * Hkv + hk) << pg.page_shift) + (slot & ((1 << pg.page_shift) - 1))) * D;
+      }
       Frag<T, E>::load(kbase + off, kf[u]);
       Frag<T, E>::load(vbase + off, vf[u]);
     }
@@ -212,10 +235,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) M = fmaxf(M, sM[w][g]);
+    const float Ms = (M == -INFINITY) ? 0.f : M;  // a split without keys (paged, short sequence)
     float L = 0.f, acc = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      const float f = exp2f(sM[w][g] - M);
+      const float f = exp2f(sM[w][g] - Ms);
       L += sL[w][g] * f;
       acc += sO[w][g][d] * f;
     }
@@ -284,11 +308,46 @@ __global__ __launch_bounds__(256) void lg_kv_append_kernel(const uint4* __restri
   }
 }
 
+// The same for a paged cache: per-sequence start positions, slots go through the page table.
+template <int LPR>
+__global__ __launch_bounds__(256) void lg_kv_paged_append_kernel(const uint4* __restrict__ kn,
+                                                                 const uint4* __restrict__ vn,
+                                                                 uint4* __restrict__ kp, uint4* __restrict__ vp,
+                                                                 const int* __restrict__ page_table,
+                                                                 const int* __restrict__ positions, int T,
+                                                                 int pages_per_seq, int page_shift, LgMask m) {
+  const int ti = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  if (ti >= T) return;
+  const int c = threadIdx.x % LPR;
+  const int Hkv = gridDim.y, hk = blockIdx.y, b = blockIdx.z;
+  const size_t src = (((size_t)b * Hkv + hk) * T + ti) * LPR + c;
+  const uint4 kx = kn[src], vx = vn[src];
+  const int pos = max(positions[b], 0);
+  const int p = pos + ti, last = pos + T - 1;
+  auto put = [&](int slot) {
+    const int page = page_table[(size_t)b * pages_per_seq + (slot >> page_shift)];
+    const size_t row = (((size_t)page * Hkv + hk) << page_shift) + (slot & ((1 << page_shift) - 1));
+    kp[row * LPR + c] = kx;
+    vp[row * LPR + c] = vx;
+  };
+  if (p < m.sink || (long long)p + m.window > last) put(p < m.sink ? p : m.sink + (p - m.sink) % m.window);
+  if (m.stride > 0) {
+    const int kb = lg_div_b(m, p);
+    if (lg_strided(m, kb)) {
+      const int slot = m.sink + m.window + (kb / m.stride) * m.b + (p - kb * m.b);
+      if ((slot >> page_shift) < pages_per_seq) put(slot);  // positions beyond the table's reach are dropped
+    }
+  }
+}
+
 template <typename T, int D>
 hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out, float* lse, void* ws,
-                        int B, int Hq, int Hkv, int C, const LgDecSegs& segs, float scale, hipStream_t s) {
-  const int valid = segs.pre[segs.n];
+                        int B, int Hq, int Hkv, int C, const LgDecSegs& segs, float scale, hipStream_t s,
+                        const LgPaged* paged) {
+  const int valid = segs.pre[segs.n];  // paged: of the longest admissible context (sizes the split)
   const bool plain = segs.n == 1 && segs.start[0] == 0;
+  LgPaged pg = {};
+  if (paged) pg = *paged;
   const int G = Hq / Hkv;
   const int splits = lg_decode_splits(B, Hkv, valid);
   const int chunk = (valid + splits - 1) / splits;
@@ -301,12 +360,15 @@ hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out
 #define LG_DECODE_LAUNCH(GT)                                                                          \
   do {                                                                                                \
     const dim3 grid(splits, Hkv*((G + GT - 1) / GT), B);                                              \
-    if (plain)                                                                                        \
-      decode_kernel<T, D, GT, false><<<grid, WAVES * 64, 0, s>>>(tq, tk, tv, to, lse, fws, Hq, Hkv, C, \
-                                                                 valid, chunk, splits, sl2, segs);    \
+    if (paged)                                                                                        \
+      decode_kernel<T, D, GT, LG_DEC_PAGED><<<grid, WAVES * 64, 0, s>>>(                              \
+          tq, tk, tv, to, lse, fws, Hq, Hkv, C, valid, chunk, splits, sl2, segs, pg);                 \
+    else if (plain)                                                                                   \
+      decode_kernel<T, D, GT, LG_DEC_PLAIN><<<grid, WAVES * 64, 0, s>>>(                              \
+          tq, tk, tv, to, lse, fws, Hq, Hkv, C, valid, chunk, splits, sl2, segs, pg);                 \
     else                                                                                              \
-      decode_kernel<T, D, GT, true><<<grid, WAVES * 64, 0, s>>>(tq, tk, tv, to, lse, fws, Hq, Hkv, C,  \
-                                                                valid, chunk, splits, sl2, segs);     \
+      decode_kernel<T, D, GT, LG_DEC_SEGS><<<grid, WAVES * 64, 0, s>>>(                               \
+          tq, tk, tv, to, lse, fws, Hq, Hkv, C, valid, chunk, splits, sl2, segs, pg);                 \
   } while (0)
   if (G == 1) LG_DECODE_LAUNCH(1);
   else if (G == 2) LG_DECODE_LAUNCH(2);
@@ -340,16 +402,49 @@ size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid) {
   return (size_t)B * Hq * splits * (D + 2) * sizeof(float);
 }
 
+// paged: NULL for a contiguous cache [B, Hkv, C, D]; else page table, lengths and geometry of a
+// paged cache [pages, Hkv, page size, D] (C unused), segs = the runs of the longest context.
 hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                             void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
-                            int dtype, float scale, hipStream_t s) {
+                            int dtype, float scale, hipStream_t s, const int* page_table, const int* seq_lens,
+                            int pages_per_seq, int page_shift, int n_max, const LgMask* cache_mask) {
+  LgPaged pg = {};
+  const LgPaged* pp = nullptr;
+  if (page_table) {
+    pg.page_table = page_table;
+    pg.seq_lens = seq_lens;
+    pg.pages_per_seq = pages_per_seq;
+    pg.page_shift = page_shift;
+    pg.n_max = n_max;
+    pg.cm = *cache_mask;
+    pp = &pg;
+  }
   if (dtype == LG_F32) {
-    return D == 64 ? launch_typed<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s)
-                   : launch_typed<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s);
+    return D == 64 ? launch_typed<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp)
+                   : launch_typed<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp);
   }
   return D == 64
-      ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s)
-      : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s);
+      ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp)
+      : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp);
+}
+
+hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                                     const int* page_table, const int* positions, int B, int Hkv,
+                                     int row_bytes, int T, int pages_per_seq, int page_shift, const LgMask& m,
+                                     hipStream_t s) {
+  const int lpr = row_bytes / 16;
+  const dim3 grid((T + 256 / lpr - 1) / (256 / lpr), Hkv, B);
+  const uint4* kn = (const uint4*)k_new;
+  const uint4* vn = (const uint4*)v_new;
+  uint4* kp = (uint4*)k_pages;
+  uint4* vp = (uint4*)v_pages;
+#define LG_PA(L) lg_kv_paged_append_kernel<L><<<grid, 256, 0, s>>>(kn, vn, kp, vp, page_table, positions, T, \
+                                                                   pages_per_seq, page_shift, m)
+  if (lpr == 8) LG_PA(8);
+  else if (lpr == 16) LG_PA(16);
+  else LG_PA(32);
+#undef LG_PA
+  return hipGetLastError();
 }
 
 hipError_t lg_launch_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,

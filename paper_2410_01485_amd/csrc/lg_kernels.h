@@ -51,7 +51,13 @@ int lg_decode_splits(int B, int Hkv, int valid);
 size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid);
 hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                             void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
-                            int dtype, float scale, hipStream_t s);
+                            int dtype, float scale, hipStream_t s, const int* page_table = nullptr,
+                            const int* seq_lens = nullptr, int pages_per_seq = 0, int page_shift = 0,
+                            int n_max = 0, const LgMask* cache_mask = nullptr);
+hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                                     const int* page_table, const int* positions, int B, int Hkv,
+                                     int row_bytes, int T, int pages_per_seq, int page_shift, const LgMask& m,
+                                     hipStream_t s);
 hipError_t lg_launch_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                                int B, int Hkv, int row_bytes, int T, int pos, int slots,
                                const LgMask& m, hipStream_t s);

@@ -54,3 +54,26 @@ def test_cache_argument_checks():
                                          lg.LG_BF16, 0.0, None) == INVALID
     assert L.lg_sparse_attn_decode(p, p, p, p, None, None, 0, 1, 1, 1, 1000, 128, 64, 192, 64, 8,
                                    lg.LG_BF16, 0.0, None) == UNSUP
+
+
+def test_paged_argument_checks():
+    L = lg.lib()
+    p = 4096
+    INVALID, NULL = 2, 1
+    # q, k_pages, v_pages, page_table, seq_lens, out, lse, ws, ws_bytes, B, Hq, Hkv, n_max, D, sink, window, block,
+    # stride, page_size, pages_per_seq, num_pages, dtype, scale, stream
+    def dec(page_size=64, pps=8, num_pages=100, table=p, **kw):
+        a = dict(n_max=400, sink=64, window=192, block=64, stride=8)
+        a.update(kw)
+        return L.lg_sparse_attn_decode_paged(p, p, p, table, p, p, None, None, 0, 2, 4, 2, a["n_max"], 128, a["sink"],
+                                             a["window"], a["block"], a["stride"], page_size, pps, num_pages,
+                                             lg.LG_BF16, 0.0, None)
+    assert dec(table=None) == NULL
+    assert dec(page_size=48) == INVALID and dec(page_size=8) == INVALID and dec(page_size=8192) == INVALID
+    assert dec(pps=3) == INVALID            # 3 pages of 64 slots cannot hold 64 + 192 + 0 slots
+    assert dec(n_max=100000, pps=8) == INVALID
+    assert dec(num_pages=0) == INVALID
+    assert L.lg_kv_paged_append(p, p, p, p, p, p, 2, 2, 128, 0, 400, 64, 192, 64, 8, 64, 8, 100, lg.LG_BF16,
+                                None) == INVALID   # T < 1
+    assert L.lg_kv_paged_append(p, p, p, p, None, p, 2, 2, 128, 1, 400, 64, 192, 64, 8, 64, 8, 100, lg.LG_BF16,
+                                None) == NULL

@@ -136,3 +136,88 @@ def test_paper_settings_full_context(sink, window, block, stride):
     wo, wl = O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(N - 1, N))
     assert_close(f32np(out), wo[:, :, N - 1], TOL_OUT[torch.bfloat16], None, "paper setting out")
     assert_close(f32np(lse), wl[:, :, N - 1], TOL_LSE[torch.bfloat16], None, "paper setting lse")
+
+
+# ------------------------------------------------------------------ paged cache, per-sequence lengths
+def paged_setup(lens, Hq, Hkv, D, sink, window, block, stride, page_size, dtype, seed):
+    """Contexts of different lengths, a page table that scatters every sequence's pages over the pool."""
+    B, n_max = len(lens), max(lens) + 8
+    slots = lg.lg_kv_cache_slots(n_max, sink, window, block, stride)
+    pps = (slots + page_size - 1) // page_size
+    num_pages = B * pps + 3
+    perm = np.random.default_rng(seed).permutation(num_pages)[:B * pps].reshape(B, pps).astype(np.int32)
+    table = torch.as_tensor(perm).to(DEV)
+    kp = torch.full((num_pages, Hkv, page_size, D), 1.0e4, dtype=dtype, device=DEV)
+    vp = torch.full_like(kp, -1.0e4)
+    ctx = [lg_synth.prefill_inputs(1, Hq, Hkv, n, D, seed + 13 * b, dtype) for b, n in enumerate(lens)]
+    return n_max, table, kp, vp, ctx
+
+
+def paged_decode(qs, kp, vp, table, lens, n_max, sink, window, block, stride):
+    q = torch.stack(qs).to(DEV)
+    B, Hq, D = q.shape
+    Hkv = kp.shape[1]
+    code = lg.LG_BF16 if q.dtype == torch.bfloat16 else lg.LG_F32
+    need = lg.decode_paged_workspace_bytes(B, Hq, Hkv, n_max, D, sink, window, block, stride, code)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    sl = torch.as_tensor(np.asarray(lens, dtype=np.int32)).to(DEV)
+    lg.lg_sparse_attn_decode_paged(q, kp, vp, table, sl, out, lse, ws, n_max, sink, window, block, stride)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("sink,window,block,stride,page_size", [
+    (16, 128, 1, 0, 16), (64, 192, 64, 8, 64), (16, 48, 16, 4, 32), (0, 64, 64, 2, 256)])
+def test_paged_varlen_decode(dtype, sink, window, block, stride, page_size):
+    lens = [1000, 37, 700, 1, 333]
+    Hq, Hkv, D = 4, 2, 128
+    n_max, table, kp, vp, ctx = paged_setup(lens, Hq, Hkv, D, sink, window, block, stride, page_size, dtype, 5)
+    for b, (q, k, v) in enumerate(ctx):  # fill sequence b's pages in a few append calls
+        pos = 0
+        for T in chunking(lens[b], 100 + b):
+            lg.lg_kv_paged_append(k[:, :, pos:pos + T].contiguous().to(DEV), v[:, :, pos:pos + T].contiguous().to(DEV),
+                                  kp, vp, table[b:b + 1], torch.tensor([pos], dtype=torch.int32, device=DEV), n_max,
+                                  sink, window, block, stride)
+            pos += T
+    # the pages of a sequence, gathered through its table row, are the oracle's cache row
+    slots = lg.lg_kv_cache_slots(n_max, sink, window, block, stride)
+    for b, (q, k, v) in enumerate(ctx):
+        wk, wv = oracle_append_all(k, v, sink, window, block, stride, slots, 1.0e4)
+        got = bits(kp[table[b].long()].permute(1, 0, 2, 3).reshape(Hkv, -1, D)[:, :slots])
+        assert np.array_equal(got, wk[0]), "pages of sequence %d" % b
+    out, lse = paged_decode([q[0, :, n - 1] for (q, _, _), n in zip(ctx, lens)], kp, vp, table, lens, n_max, sink,
+                            window, block, stride)
+    for b, ((q, k, v), n) in enumerate(zip(ctx, lens)):
+        wo, wl = O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(n - 1, n))
+        assert_close(f32np(out[b]), wo[0, :, n - 1], TOL_OUT[dtype], None, "paged seq %d out" % b)
+        assert_close(f32np(lse[b]), wl[0, :, n - 1], TOL_LSE[dtype], None, "paged seq %d lse" % b)
+
+
+def test_paged_generation_step_all_sequences_at_once():
+    # every sequence appends one token at its own position in ONE call, then decodes at its own length
+    sink, window, block, stride, page_size = 32, 64, 32, 3, 64
+    lens = [400, 95, 250]
+    Hq, Hkv, D, steps = 4, 4, 64, 70
+    dtype = torch.bfloat16
+    full = [n + steps for n in lens]
+    n_max, table, kp, vp, ctx = paged_setup(full, Hq, Hkv, D, sink, window, block, stride, page_size, dtype, 9)
+    for b, (q, k, v) in enumerate(ctx):
+        lg.lg_kv_paged_append(k[:, :, :lens[b]].contiguous().to(DEV), v[:, :, :lens[b]].contiguous().to(DEV), kp, vp,
+                              table[b:b + 1], torch.zeros(1, dtype=torch.int32, device=DEV), n_max, sink, window,
+                              block, stride)
+    want = [O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(lens[b], lens[b] + steps))
+            for b, (q, k, v) in enumerate(ctx)]
+    for s in range(steps):
+        pos = [n + s for n in lens]
+        kn = torch.stack([k[0, :, p:p + 1] for (_, k, _), p in zip(ctx, pos)]).to(DEV)
+        vn = torch.stack([v[0, :, p:p + 1] for (_, _, v), p in zip(ctx, pos)]).to(DEV)
+        lg.lg_kv_paged_append(kn, vn, kp, vp, table, torch.as_tensor(np.asarray(pos, dtype=np.int32)).to(DEV), n_max,
+                              sink, window, block, stride)
+        out, lse = paged_decode([q[0, :, p] for (q, _, _), p in zip(ctx, pos)], kp, vp, table, [p + 1 for p in pos],
+                                n_max, sink, window, block, stride)
+        for b, p in enumerate(pos):
+            assert_close(f32np(out[b]), want[b][0][0, :, p], TOL_OUT[dtype], None, "step %d seq %d out" % (s, b))
+            assert_close(f32np(lse[b]), want[b][1][0, :, p], TOL_LSE[dtype], None, "step %d seq %d lse" % (s, b))
