@@ -58,19 +58,25 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// E elements of T loaded as one 16-byte vector, widened to float.  The loads are marked
+// non-temporal: every cache byte is used exactly once per call, so keeping it in L2 / the
+// memory-side cache only evicts something else (measured: 181 -> 164 us at B16 x 32 heads x
+// 4160 slots).
+typedef unsigned lg_u32x4 __attribute__((ext_vector_type(4)));
+typedef float lg_f32x4 __attribute__((ext_vector_type(4)));
 template <typename T, int E>
-struct Frag;  // E elements of T loaded as one 16-byte vector, widened to float
+struct Frag;
 template <>
 struct Frag<float, 4> {
   __device__ static void load(const void* p, float* f) {
-    const float4 x = *reinterpret_cast<const float4*>(p);
+    const lg_f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const lg_f32x4*>(p));
     f[0] = x.x; f[1] = x.y; f[2] = x.z; f[3] = x.w;
   }
 };
 template <>
 struct Frag<__hip_bfloat16, 8> {
   __device__ static void load(const void* p, float* f) {
-    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const lg_u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const lg_u32x4*>(p));
     const unsigned w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
