@@ -18,9 +18,15 @@
  * counts, the paper's retained-token budgets (Section 4.1), library causal
  * attention when window >= N, library masked attention and autograd on small
  * shapes, finite differences, and softmax invariants.
+ * The reduced-KV-cache bookkeeping (lgo_ring_append and friends) is pinned by
+ * tests/test_oracle_cache.py: after appending tokens 0..N-1 every live key of
+ * row N-1 sits in the slot the layout rule names, the token-granular case equals
+ * the slot-map build, batching does not matter, and the slot counts reproduce
+ * the paper's 2112 / 2048-token budgets.
  * Parity unpinned: the residue of the strided columns (kb % stride ==
- * stride-1) and the inclusion of the query's own block in the window are
- * conventions the paper does not state.
+ * stride-1), the inclusion of the query's own block in the window, and the
+ * placement of the retained strided blocks after the rolling window in a cache
+ * row are conventions the paper does not state.
  */
 #include <math.h>
 #include <stdint.h>

@@ -110,3 +110,18 @@ def test_config4_full_size_sampled():
     # Llama-2-70B shape, GQA 64/8, N=131072, sink 64 + window 4096
     sampled_full_size(64, 8, 131072, 64, 4096, 1, 0, 20241005, heads=[0, 7, 8, 37, 63],
                       row_starts=[0, 4000, 4150, 65536 + 77, 131072])
+
+
+def test_work_is_enqueued_on_the_callers_stream():
+    # the binding hands torch's current stream to the library: a side stream must give the same bytes
+    q, k, v = lg_synth.prefill_inputs(1, 4, 2, 3000, 128, 61, torch.bfloat16)
+    a, la = run_fwd(q, k, v, 64, 512)
+    side = torch.cuda.Stream()
+    qd, kd, vd = (x.to(DEV) for x in (q, k, v))
+    out = torch.empty_like(qd)
+    lse = torch.empty(1, 4, 3000, dtype=torch.float32, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        lg.lg_sparse_attn_fwd(qd, kd, vd, out, lse, 64, 512)
+    side.synchronize()
+    assert torch.equal(out, a) and torch.equal(lse, la)
