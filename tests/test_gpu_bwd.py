@@ -167,3 +167,32 @@ def test_paper_block_settings_full_size_sampled():
         assert_close(f32np(dk[0, h, keys[0]:keys[1]]), w["dk"][0, 0, keys[0]:keys[1]], tol, rel, "paper dk h%d" % h)
         assert_close(f32np(dv[0, h, keys[0]:keys[1]]), w["dv"][0, 0, keys[0]:keys[1]], tol, rel, "paper dv h%d" % h)
         assert_close(f32np(out[0, h, rows[0]:rows[1]]), w["out"][0, 0, rows[0]:rows[1]], tol, rel, "paper out h%d" % h)
+
+
+def test_one_million_tokens_sampled():
+    """Index arithmetic at 2^20 tokens (8x the benchmark length), one head pair with GQA: forward and backward
+    against the oracle on sampled rows and on sampled keys outside the sink (the sink keys would need the
+    whole forward on the CPU)."""
+    B, Hq, Hkv, N, D, sink, window = 1, 2, 1, 1 << 20, 128, 64, 4096
+    q, k, v, g = lg_synth.prefill_inputs(B, Hq, Hkv, N, D, 20241010, torch.bfloat16, with_dout=True, device=DEV)
+    out = torch.empty_like(q)
+    lse = torch.empty(B, Hq, N, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window)
+    ws = torch.empty(lg.bwd_workspace_bytes(B, Hq, Hkv, N, D, sink, window, 1, 0, lg.LG_BF16), dtype=torch.uint8,
+                     device=DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window)
+    torch.cuda.synchronize()
+    for t in (out, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    tol, rel = TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16]
+    a = [f32np(x) for x in (q, k, v, g)]
+    for rows, keys in (((600001, 600041), (777770, 777810)), ((N - 40, N), (N - 40, N))):
+        print("rows", rows, "keys", keys, flush=True)
+        w = O.bwd(*a, sink, window, rows=rows, keys=keys)
+        r, c = slice(*rows), slice(*keys)
+        assert_close(f32np(out[0, :, r]), w["out"][0, :, r], tol, rel, "1M out")
+        assert_close(f32np(lse[0, :, r]), w["lse"][0, :, r], 2e-3, None, "1M lse")
+        assert_close(f32np(dq[0, :, r]), w["dq"][0, :, r], tol, rel, "1M dq")
+        assert_close(f32np(dk[0, :, c]), w["dk"][0, :, c], tol, rel, "1M dk")
+        assert_close(f32np(dv[0, :, c]), w["dv"][0, :, c], tol, rel, "1M dv")
