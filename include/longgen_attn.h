@@ -257,6 +257,17 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
                       int32_t* col_idx, uint8_t* kind, size_t cap,
                       size_t* rows, size_t* needed);
 
+/*
+ * Host-only: the ORDER in which the bf16 kernels visit the live tiles of one row of the tile map
+ * (row = query tile for transposed == 0, key tile for transposed == 1).  Patterns without
+ * strided columns walk their contiguous run of tiles rotated (see lg_debug_tile_map); for a key
+ * tile the window part comes first (rotated), then the column part in increasing order.
+ * order: HOST array of cap entries (may be NULL with cap = 0); *count receives the number of
+ * tiles.  The set of tiles equals the row of lg_debug_tile_map.
+ */
+int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int transposed, int row,
+                       int32_t* order, size_t cap, size_t* count);
+
 #ifdef __cplusplus
 }
 #endif

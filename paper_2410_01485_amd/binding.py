@@ -63,6 +63,8 @@ def lib():
         L.lg_kv_paged_append.restype = _i
         L.lg_debug_decode_segments.argtypes = [_i] * 5 + [ctypes.POINTER(_i), _vp, _vp]
         L.lg_debug_decode_segments.restype = _i
+        L.lg_debug_tile_walk.argtypes = [_i] * 7 + [_vp, _sz, ctypes.POINTER(_sz)]
+        L.lg_debug_tile_walk.restype = _i
         L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
                                                    _vp, _vp, _sz, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
         L.lg_debug_tile_map.restype = _i
@@ -288,3 +290,18 @@ def lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed):
     if st != 0:
         raise LgError(st, "lg_debug_tile_map")
     return tq.value, tk.value, row_ptr, col[:need.value], kind[:need.value]
+
+
+def lg_debug_tile_walk(N, sink, window, block, stride, transposed, row):
+    """Host-only: the order in which the bf16 kernels visit the live tiles of one row of the tile map."""
+    import numpy as np
+    cnt = _sz(0)
+    st = lib().lg_debug_tile_walk(N, sink, window, block, stride, transposed, row, None, 0, ctypes.byref(cnt))
+    if st != 0:
+        raise LgError(st, "lg_debug_tile_walk")
+    order = np.zeros(max(cnt.value, 1), dtype=np.int32)
+    st = lib().lg_debug_tile_walk(N, sink, window, block, stride, transposed, row, order.ctypes.data, cnt.value,
+                                  ctypes.byref(cnt))
+    if st != 0:
+        raise LgError(st, "lg_debug_tile_walk")
+    return order[:cnt.value]

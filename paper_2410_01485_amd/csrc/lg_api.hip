@@ -357,4 +357,44 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
   return LG_OK;
 }
 
+int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int transposed, int row,
+                       int32_t* order, size_t cap, size_t* count) {
+  if (!count) return LG_ERR_NULL;
+  int st = check_common(1, 1, 1, N, 64, sink, window, block, stride, LG_BF16);
+  if (st != LG_OK) return st;
+  const LgMask m = lg_make_mask(N, sink, window, block, stride);
+  const int Tq = transposed ? LG_BF16_BTQ : LG_BF16_TQ, Tk = transposed ? LG_BF16_BTK : LG_BF16_TK;
+  const int nrows = transposed ? (N + Tk - 1) / Tk : (N + Tq - 1) / Tq;
+  if (row < 0 || row >= nrows) return LG_ERR_INVALID_ARG;
+  size_t n = 0;
+  auto emit = [&](int t) {
+    if (order && n < cap) order[n] = t;
+    ++n;
+  };
+  if (!transposed) {
+    const int q0 = row * Tq, q1 = (q0 + Tq - 1 < N - 1) ? q0 + Tq - 1 : N - 1;
+    const LgQSched qs = lg_qsched_init(m, q0, q1);
+    if (m.b == 1 && m.stride == 0) {  // the token-granular kernels' rotated walk
+      const LgQWalk w = lg_qwalk_init(qs);
+      for (int t = lg_qwalk_first(w); t >= 0; t = lg_qwalk_next(w, t)) emit(t);
+    } else {
+      for (int t = lg_qsched_next(m, qs, -1); t >= 0; t = lg_qsched_next(m, qs, t)) emit(t);
+    }
+  } else {
+    const int k0 = row * Tk, k1 = (k0 + Tk - 1 < N - 1) ? k0 + Tk - 1 : N - 1;
+    int lo, hi;
+    lg_qtile_range(m, k0, k1, Tq, &lo, &hi);
+    const int hw = lg_qtile_window_hi(m, k1, Tq);  // window part [lo, hw], walked rotated
+    const int len = hw - lo + 1;
+    int u = lo + (len - lo % len) % len;
+    for (int x = 0; x < len; ++x) {
+      emit(u);
+      u = (u == hw) ? lo : u + 1;
+    }
+    for (int c = hw + 1; c <= hi; ++c) emit(c);  // column part (its own workgroups, or the same one)
+  }
+  *count = n;
+  return LG_OK;
+}
+
 }  // extern "C"

@@ -88,3 +88,26 @@ def test_live_tile_totals_of_benchmark_configs():
     per_row = np.diff(rp)
     assert per_row.max() <= 1 + (4096 + tq) // tk + 1
     assert int(per_row[-1]) == 1 + (4096 + tq - 1 + tk - 1) // tk
+
+
+@pytest.mark.parametrize("N,sink,window,block,stride", CASES + [(5000, 64, 1000, 1, 0), (20000, 64, 4096, 1, 0),
+                                                                (4000, 0, 64, 64, 4), (3000, 300, 100, 1, 0)])
+@pytest.mark.parametrize("transposed", [0, 1])
+def test_walk_order_visits_exactly_the_rows_tiles(N, sink, window, block, stride, transposed):
+    # the kernels do not walk a row of the tile map in increasing order (rotated walks): whatever the
+    # order, it must be a permutation of the row
+    tq, tk, rp, ci, kd = lg.lg_debug_tile_map(N, sink, window, block, stride, lg.LG_BF16, transposed)
+    for r in range(len(rp) - 1):
+        order = lg.lg_debug_tile_walk(N, sink, window, block, stride, transposed, r)
+        assert sorted(order.tolist()) == ci[rp[r]:rp[r + 1]].tolist(), (r, order[:8])
+
+
+def test_rotated_walks_align_neighbours():
+    # token pattern, steady state: at step x every query tile is at the key tile congruent to x modulo
+    # its run length, so neighbouring query tiles are on the same key tile wherever their runs overlap
+    N, sink, window = 40000, 64, 4096
+    a = lg.lg_debug_tile_walk(N, sink, window, 1, 0, 0, 100)
+    b = lg.lg_debug_tile_walk(N, sink, window, 1, 0, 0, 101)
+    assert len(a) == len(b) == 69 and a[0] == 0 and b[0] == 0      # sink tile first, then the run of 68
+    same = sum(int(x == y) for x, y in zip(a[1:], b[1:]))
+    assert same == 64                                                # runs overlap in 64 of 68 tiles
