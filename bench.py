@@ -211,7 +211,7 @@ def main():
         it[0] += 1
         lg.lg_sparse_attn_decode(a, b_, c_, dout, dlse, dws, dN, dsink, dwin)
 
-    for _ in range(max(W, 3)):
+    for _ in range(max(W, 10)):  # the memory clock needs a few launches to settle after the prefill part
         dstep()
     torch.cuda.synchronize()
     reps = max(K * 5, 30)
@@ -229,6 +229,26 @@ def main():
               "roofline": {"bound": "hbm", "achieved": round(dec_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4),
                            "traffic": sum(MEASURED_HBM_BYTES["decode_kernel"])}}
+
+    # (extras) A/B: the paper's decode design, work split over the head dimension instead of the slots
+    if not args.no_extras:
+        for _ in range(3):
+            a, b_, c_ = sets[it[0] % 3]
+            it[0] += 1
+            sd_ws = lg.lg_debug_decode_split_headdim(a, b_, c_, dout, dlse, dN, dsink, dwin)
+        e0.record()
+        for _ in range(reps):
+            a, b_, c_ = sets[it[0] % 3]
+            it[0] += 1
+            lg.lg_debug_decode_split_headdim(a, b_, c_, dout, dlse, dN, dsink, dwin)
+        e1.record()
+        torch.cuda.synchronize()
+        sd_ms = e0.elapsed_time(e1) / reps
+        decode["split_head_dim_variant"] = {
+            "what": "same workload, head dimension split in 2 across workgroups (two passes, partial scores "
+                    "through a workspace); includes the workspace allocation of the Python helper",
+            "us_per_call": round(sd_ms * 1e3, 2), "gbs": round(dec_bytes / (sd_ms * 1e-3) / 1e9, 1)}
+        del sd_ws
 
     # (extras) the block-sparse + sink + window pattern of Section 4.1 over the same cache tensors:
     # 64-token blocks, 1 sink block, 32 local blocks, one retained block per 64 (4160 slots too)

@@ -228,6 +228,21 @@ int lg_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void
                        int page_size, int pages_per_seq, int num_pages, int dtype, void* hip_stream);
 
 /*
+ * Measurement aid, not a product path: decode over the token-granular cache of
+ * lg_sparse_attn_decode with the work split over the HEAD DIMENSION instead of the cache slots,
+ * the design the paper describes for its decode kernel (Section 3.2, second paragraph: the loading
+ * of the head dimension is split across thread blocks).  Two halves of D, two passes (partial
+ * scores through the workspace, then softmax and the V slice).  Same arguments and result as
+ * lg_sparse_attn_decode with block <= 1, stride == 0; workspace from the call below.  Exists so
+ * that the two splits can be timed against each other on the same inputs.
+ */
+size_t lg_debug_decode_split_headdim_workspace_bytes(int B, int Hq, int sink, int window);
+int lg_debug_decode_split_headdim(const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
+                                  void* workspace, size_t workspace_bytes,
+                                  int B, int Hq, int Hkv, int N, int D, int sink, int window,
+                                  int dtype, float scale, void* hip_stream);
+
+/*
  * Host-only: the runs of consecutive cache slots a decode step at context length N reads
  * (at most 4; start/len are HOST arrays of 4 entries; *nseg receives the count).  Runs the
  * same source the decode launch uses (no GPU needed).

@@ -61,6 +61,10 @@ def lib():
         L.lg_sparse_attn_decode_paged.restype = _i
         L.lg_kv_paged_append.argtypes = [_vp] * 6 + [_i] * 12 + [_i, _vp]
         L.lg_kv_paged_append.restype = _i
+        L.lg_debug_decode_split_headdim_workspace_bytes.argtypes = [_i] * 4
+        L.lg_debug_decode_split_headdim_workspace_bytes.restype = _sz
+        L.lg_debug_decode_split_headdim.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 7 + [_i, _f, _vp]
+        L.lg_debug_decode_split_headdim.restype = _i
         L.lg_debug_decode_segments.argtypes = [_i] * 5 + [ctypes.POINTER(_i), _vp, _vp]
         L.lg_debug_decode_segments.restype = _i
         L.lg_debug_tile_walk.argtypes = [_i] * 7 + [_vp, _sz, ctypes.POINTER(_sz)]
@@ -305,3 +309,18 @@ def lg_debug_tile_walk(N, sink, window, block, stride, transposed, row):
     if st != 0:
         raise LgError(st, "lg_debug_tile_walk")
     return order[:cnt.value]
+
+
+def lg_debug_decode_split_headdim(q, k_cache, v_cache, out, lse, N, sink, window, scale=0.0):
+    """Measurement aid: decode with the work split over the head dimension (the paper's design)."""
+    import torch
+    B, Hq, D = q.shape
+    Hkv = k_cache.shape[1]
+    _check(k_cache, B, Hkv, sink + window, D), _check(v_cache, B, Hkv, sink + window, D), _check(out, B, Hq, D)
+    need = int(lib().lg_debug_decode_split_headdim_workspace_bytes(B, Hq, sink, window))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = lib().lg_debug_decode_split_headdim(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(ws),
+                                             need, B, Hq, Hkv, N, D, sink, window, _dtype_code(q), scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_debug_decode_split_headdim")
+    return ws

@@ -284,6 +284,30 @@ int lg_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
 }
 
+size_t lg_debug_decode_split_headdim_workspace_bytes(int B, int Hq, int sink, int window) {
+  if (B < 1 || Hq < 1 || sink < 0 || window < 1 || (double)sink + (double)window > 1073741824.0) return 0;
+  return lg_decode_split_headdim_workspace_bytes(B, Hq, sink + window);
+}
+
+int lg_debug_decode_split_headdim(const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
+                                  void* workspace, size_t workspace_bytes,
+                                  int B, int Hq, int Hkv, int N, int D, int sink, int window,
+                                  int dtype, float scale, void* hip_stream) {
+  if (!q || !k_cache || !v_cache || !out || !workspace) return LG_ERR_NULL;
+  int st = check_decode(B, Hq, Hkv, N, D, sink, window, 1, 0, dtype);
+  if (st != LG_OK) return st;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(lse) ||
+      !aligned16(workspace))
+    return LG_ERR_INVALID_ARG;
+  const int C = sink + window;
+  if (workspace_bytes < lg_decode_split_headdim_workspace_bytes(B, Hq, C)) return LG_ERR_WORKSPACE;
+  const LgShape sh = make_shape(B, Hq, Hkv, N, D, scale);
+  hipError_t e = lg_launch_decode_split_headdim(q, k_cache, v_cache, out, lse, workspace, B, Hq, Hkv, C,
+                                                N < C ? N : C, D, dtype, sh.scale,
+                                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
 int lg_debug_decode_segments(int N, int sink, int window, int block, int stride,
                              int* nseg, int32_t* start, int32_t* len) {
   if (!nseg || !start || !len) return LG_ERR_NULL;

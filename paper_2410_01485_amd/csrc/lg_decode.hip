@@ -346,6 +346,100 @@ __global__ __launch_bounds__(256) void lg_kv_paged_append_kernel(const uint4* __
   }
 }
 
+// ---------------------------------------------------------------- measurement aid
+// The paper's decode design splits the LOADING OF THE HEAD DIMENSION across thread blocks instead
+// of the cache slots (Section 3.2, second paragraph).  Read here as: block s of S loads dims
+// [s*D/S, (s+1)*D/S) of every K row and produces partial scores; a second pass sums the S partial
+// scores of a slot, runs the softmax and multiplies with its own dim slice of V.  K and V are
+// still read once; the partial scores (S * slots floats per head) travel through the workspace.
+// Kept as an A/B against the split over slots above, not used by any product entry point.
+template <typename T, int D, int S>
+__global__ __launch_bounds__(256) void decode_sd_scores_kernel(const T* __restrict__ q, const T* __restrict__ kc,
+                                                               float* __restrict__ part, int Hq, int Hkv, int C,
+                                                               int valid, float scale_log2e) {
+  constexpr int E = 16 / sizeof(T), DS = D / S, LPR = DS / E, RPB = 256 / LPR;
+  const int G = Hq / Hkv;
+  const int s = blockIdx.y, bh = blockIdx.z, b = bh / Hkv, hk = bh % Hkv;
+  const int slot = blockIdx.x * RPB + threadIdx.x / LPR;
+  const int c = threadIdx.x % LPR;
+  const int sl = min(slot, valid - 1);
+  float kf[E];
+  Frag<T, E>::load(kc + (((size_t)b * Hkv + hk) * C + sl) * D + s * DS + c * E, kf);
+  for (int g = 0; g < G; ++g) {
+    const int hq = hk * G + g;
+    float qf[E];
+    Frag<T, E>::load(q + ((size_t)b * Hq + hq) * D + s * DS + c * E, qf);
+    float a = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) a = fmaf(qf[e], kf[e], a);
+#pragma unroll
+    for (int x = 1; x < LPR; x <<= 1) a += __shfl_xor(a, x);
+    if (c == 0 && slot < valid) part[(((size_t)b * Hq + hq) * S + s) * C + slot] = a * scale_log2e;
+  }
+}
+
+template <typename T, int D, int S>
+__global__ __launch_bounds__(256) void decode_sd_out_kernel(const float* __restrict__ part, const T* __restrict__ vc,
+                                                            T* __restrict__ out, float* __restrict__ lse, int Hq,
+                                                            int Hkv, int C, int valid) {
+  constexpr int E = 16 / sizeof(T), DS = D / S, LPR = DS / E, RPB = 256 / LPR;
+  __shared__ float sM[RPB], sL[RPB], sO[RPB][DS];
+  const int G = Hq / Hkv;
+  const int s = blockIdx.x, row = blockIdx.y, b = row / Hq, hq = row % Hq, hk = hq / G;
+  const int r = threadIdx.x / LPR, c = threadIdx.x % LPR;
+  const float* pr = part + (size_t)row * S * C;
+  const T* vb = vc + (((size_t)b * Hkv + hk) * C) * D + s * DS + c * E;
+  float m = -INFINITY, l = 0.f, o[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) o[e] = 0.f;
+  for (int slot = r; slot < valid; slot += RPB) {
+    float sc = 0.f;
+#pragma unroll
+    for (int x = 0; x < S; ++x) sc += pr[(size_t)x * C + slot];
+    float vf[E];
+    Frag<T, E>::load(vb + (size_t)slot * D, vf);
+    const float mn = fmaxf(m, sc);
+    const float alpha = exp2f(m - mn), p = exp2f(sc - mn);
+    m = mn;
+    l = l * alpha + p;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = fmaf(p, vf[e], o[e] * alpha);
+  }
+  if (c == 0) {
+    sM[r] = m;
+    sL[r] = l;
+  }
+#pragma unroll
+  for (int e = 0; e < E; ++e) sO[r][c * E + e] = o[e];
+  __syncthreads();
+  for (int d = threadIdx.x; d < DS; d += 256) {
+    float M = -INFINITY;
+    for (int x = 0; x < RPB; ++x) M = fmaxf(M, sM[x]);
+    float L = 0.f, acc = 0.f;
+    for (int x = 0; x < RPB; ++x) {
+      const float f = (sM[x] == -INFINITY) ? 0.f : exp2f(sM[x] - M);
+      L += sL[x] * f;
+      acc += sO[x][d] * f;
+    }
+    store_out(out + (size_t)row * D + s * DS + d, acc / L);
+    if (lse != nullptr && s == 0 && d == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_split_headdim(const void* q, const void* kc, const void* vc, void* out, float* lse, void* ws,
+                                int B, int Hq, int Hkv, int C, int valid, float scale, hipStream_t s) {
+  constexpr int S = 2, E = 16 / sizeof(T), RPB = 256 / ((D / S) / E);
+  const float sl2 = scale * 1.44269504088896340736f;
+  decode_sd_scores_kernel<T, D, S><<<dim3((valid + RPB - 1) / RPB, S, B * Hkv), 256, 0, s>>>(
+      (const T*)q, (const T*)kc, (float*)ws, Hq, Hkv, C, valid, sl2);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  decode_sd_out_kernel<T, D, S><<<dim3(S, B * Hq), 256, 0, s>>>((const float*)ws, (const T*)vc, (T*)out, lse, Hq,
+                                                                Hkv, C, valid);
+  return hipGetLastError();
+}
+
 template <typename T, int D>
 hipError_t launch_typed(const void* q, const void* kc, const void* vc, void* out, float* lse, void* ws,
                         int B, int Hq, int Hkv, int C, const LgDecSegs& segs, float scale, hipStream_t s,
@@ -432,6 +526,21 @@ hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void*
   return D == 64
       ? launch_typed<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp)
       : launch_typed<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, segs, scale, s, pp);
+}
+
+// Workspace: S = 2 partial score rows of C floats per (b, hq).
+size_t lg_decode_split_headdim_workspace_bytes(int B, int Hq, int C) { return (size_t)B * Hq * 2 * C * sizeof(float); }
+
+hipError_t lg_launch_decode_split_headdim(const void* q, const void* kc, const void* vc, void* out, float* lse,
+                                          void* ws, int B, int Hq, int Hkv, int C, int valid, int D, int dtype,
+                                          float scale, hipStream_t s) {
+  if (dtype == LG_F32) {
+    return D == 64 ? launch_split_headdim<float, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
+                   : launch_split_headdim<float, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
+  }
+  return D == 64
+      ? launch_split_headdim<__hip_bfloat16, 64>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s)
+      : launch_split_headdim<__hip_bfloat16, 128>(q, kc, vc, out, lse, ws, B, Hq, Hkv, C, valid, scale, s);
 }
 
 hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,

@@ -83,3 +83,22 @@ def test_config5_full_size():
         wo, wl = O.decode(f32np(q[b:b + 1]), f32np(kc[b:b + 1]), f32np(vc[b:b + 1]), N, sink, window)
         assert_close(f32np(out[b:b + 1]), wo, TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16], "cfg5 out b%d" % b)
         assert_close(f32np(lse[b:b + 1]), wl, TOL_LSE[torch.bfloat16], None, "cfg5 lse b%d" % b)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("D,Hq,Hkv,N", [(128, 4, 4, 5000), (64, 8, 2, 5000), (128, 2, 1, 37), (128, 3, 3, 1)])
+def test_split_over_head_dim_variant_matches_oracle(dtype, D, Hq, Hkv, N):
+    # the measurement aid that splits the head dimension (the paper's decode design) computes the same thing
+    B, sink, window = 2, 4, 300
+    q, kc, vc = lg_synth.decode_inputs(B, Hq, Hkv, sink + window, D, 17, dtype)
+    valid = min(N, sink + window)
+    kc[:, :, valid:] = 1.0e4
+    vc[:, :, valid:] = -1.0e4
+    qd, kd, vd = (x.to(DEV) for x in (q, kc, vc))
+    out = torch.full_like(qd, float("nan"))
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    lg.lg_debug_decode_split_headdim(qd, kd, vd, out, lse, N, sink, window)
+    torch.cuda.synchronize()
+    wo, wl = O.decode(f32np(q), f32np(kc), f32np(vc), N, sink, window)
+    assert_close(f32np(out), wo, TOL_OUT[dtype], TOL_REL[dtype], "split-D decode out")
+    assert_close(f32np(lse), wl, TOL_LSE[dtype], None, "split-D decode lse")
