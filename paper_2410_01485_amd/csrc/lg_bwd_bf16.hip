@@ -214,8 +214,9 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 // Column keys (sink tokens, keys of strided block columns) are seen by every later query.
 // The query range of a key tile therefore has a dense window part (like every tile) and, if it
 // holds column keys, a long column part: all later rows, but only its column keys live.
-// With one column group per head (the sink of a sink + window pattern) the tile that holds it
-// simply runs its whole range and is launched first.  With more (strided patterns) the column
+// With one column group per head (the sink of a sink + window pattern) and no GQA the tile that
+// holds it simply runs its whole range and is launched first.  Otherwise (strided patterns, or G
+// query heads per kv head, which one workgroup would have to walk one after the other) the column
 // parts are split off: the COLUMN instance of the kernel packs the 64-key column groups four at
 // a time into virtual 256-key tiles, so that all 8 waves have live keys and a Q / dO tile is
 // used by 256 keys again, cuts their query range into chunks of LG_COL_CHUNK tiles that run as
@@ -567,7 +568,9 @@ ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t delta_byte
       if (first < 0) first = grp;
       ++c.ncol;
     }
-  if (c.ncol < 2) c.ncol = 0;  // a lone group (the sink) stays with its key tile, launched first
+  // a lone group (the sink) of a head without GQA stays with its key tile, which is launched first;
+  // with G query heads per kv head that workgroup would run G times as long as everything else
+  if (c.ncol < 2 && sh.Hq == sh.Hkv) c.ncol = 0;
   c.nchunk = 0;
   if (c.ncol > 0) {  // the first group has the longest column part
     const int t0 = (first * 64 / LG_BF16_BTK) * LG_BF16_BTK;

@@ -96,7 +96,9 @@ def test_strided_columns_long_context(B, Hq, Hkv, N, D, sink, window, block, str
 
 
 def test_bwd_deterministic():
-    q, k, v, g = lg_synth.prefill_inputs(1, 4, 2, 900, 128, 9, torch.bfloat16, with_dout=True)
+    # sink + window without GQA has no atomics anywhere: bit-identical from run to run (the partial dk/dv
+    # sums of column keys in strided or GQA calls are added with float atomics, in no fixed order)
+    q, k, v, g = lg_synth.prefill_inputs(1, 4, 4, 900, 128, 9, torch.bfloat16, with_dout=True)
     a = run_fwd_bwd(q, k, v, g, 64, 300)
     b = run_fwd_bwd(q, k, v, g, 64, 300)
     for x, y in zip(a, b):
