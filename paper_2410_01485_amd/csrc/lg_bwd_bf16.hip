@@ -1,7 +1,9 @@
 // lg_bwd_bf16.hip — bf16 backward on the gfx950 matrix cores (paper Section 3.2: the
 // backward step skips masked key blocks just like the forward; Table 1 counts both).
 //
-// Two kernels after the Delta pre-pass, both free of atomics and deterministic.  Tiles
+// Two kernels after the Delta pre-pass.  Sink + window without GQA uses no atomics and is
+// bit-reproducible; strided patterns and GQA add float32 partial dk/dv sums of the column keys
+// with atomics (see the dk/dv section).  Tiles
 // travel global -> LDS directly (row-major, swizzled; lg_swz.h) and are read both with the
 // contraction over dims (row reads) and with the contraction over tile rows (transposing
 // LDS reads), so no tile is ever stored twice.
