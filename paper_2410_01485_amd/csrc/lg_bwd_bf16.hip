@@ -249,7 +249,7 @@ __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4) {
 template <int D, bool TOKEN, bool COLUMN>
 __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
     int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
     float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
@@ -276,6 +276,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 
   const int G = Hq / Hkv;
   const int N = m.N;
+  const float sl2 = scale * LOG2E;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -387,8 +388,8 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint32_t st = lds0 + VRES + buf * STAGE;
     // the small per-row loads go first: anything the compiler makes them wait for must not
     // include the tile loads issued below
-    if (wave < 2) {  // wave 0: lse rows, wave 1: Delta rows (64 floats each)
-      const float* src = (wave == 0 ? lse : delta) + row0 + min(q0 + lane, N - 1);
+    if (wave < 2) {  // wave 0: lse * log2(e) rows, wave 1: Delta rows (64 floats each)
+      const float* src = (wave == 0 ? lse2 : delta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
     dma.issue(q + (row0 + q0) * D, N - q0, st);
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const int r = 4 * r4 + t;
-            float pv = __builtin_amdgcn_exp2f(fmaf(sc[r], scale, -lv[t]) * LOG2E);
+            float pv = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -lv[t]));
             if (!full && dead(qb, r)) pv = 0.f;
             p[r] = pv;
           }
@@ -559,7 +560,7 @@ struct ColumnLayout {
   int nkt, ngroups, ncol, nchunk;  // ncol = 0: no column parts are split off
   size_t tab_off, pdk_off, pdv_off, end;
 };
-ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t delta_bytes) {
+ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t head_bytes) {
   ColumnLayout c;
   c.nkt = (sh.N + LG_BF16_BTK - 1) / LG_BF16_BTK;
   c.ngroups = (sh.N + 63) / 64;
@@ -580,7 +581,7 @@ ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t delta_byte
     const int far = (sh.N - 1) / LG_BF16_BTQ - lg_qtile_window_hi(m, t1, LG_BF16_BTQ);
     c.nchunk = (far + LG_COL_CHUNK - 1) / LG_COL_CHUNK;
   }
-  c.tab_off = delta_bytes;
+  c.tab_off = head_bytes;  // after the per-row arrays (Delta, lse * log2(e))
   const size_t tab = (((size_t)2 * c.ngroups * sizeof(int)) + 255) & ~(size_t)255;
   const size_t part = (size_t)sh.B * sh.Hkv * c.ncol * 64 * sh.D * sizeof(float);
   c.pdk_off = c.tab_off + (c.ncol > 0 ? tab : 0);
@@ -590,17 +591,20 @@ ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t delta_byte
 }
 }  // namespace
 
-size_t lg_bwd_bf16_workspace_bytes(const LgShape& sh, const LgMask& m, size_t delta_bytes) {
-  return column_layout(sh, m, delta_bytes).end;
+size_t lg_bwd_bf16_workspace_bytes(const LgShape& sh, const LgMask& m, size_t head_bytes) {
+  return column_layout(sh, m, head_bytes).end;
 }
 
 hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const void* out,
                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
                               void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
                               hipEvent_t* ev) {
+  // workspace: Delta | lse * log2(e) | column tables and partial sums
+  const size_t row_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
   float* delta = (float*)ws;
+  float* lse2 = (float*)((char*)ws + row_bytes);
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = lg_launch_delta(dout, out, delta, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
+  hipError_t e = lg_launch_delta(dout, out, delta, lse, lse2, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const uint16_t* uq = (const uint16_t*)q;
@@ -630,8 +634,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (ev) (void)hipEventRecord(ev[2], s);
   }
   {
-    const size_t delta_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
-    const ColumnLayout cl = column_layout(sh, m, delta_bytes);
+    const ColumnLayout cl = column_layout(sh, m, 2 * row_bytes);
     const int nkt = cl.nkt;
     const long long tl = (long long)nkt * sh.Hkv * sh.B;
     if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
@@ -642,7 +645,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     float* pdk = (float*)((char*)ws + cl.pdk_off);
     float* pdv = (float*)((char*)ws + cl.pdv_off);
 #define LG_DKDV_LAUNCH(DD, TT, CC, GRID)                                                                  \
-  dkdv_bf16_kernel<DD, TT, CC><<<GRID, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dk,               \
+  dkdv_bf16_kernel<DD, TT, CC><<<GRID, 512, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,              \
                                                     (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,  \
                                                     per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol,     \
                                                     cl.nchunk)
