@@ -28,6 +28,8 @@
 #include "lg_mfma.h"
 #include "lg_swz.h"
 
+#include <utility>
+
 namespace {
 
 constexpr float LOG2E = 1.44269504088896340736f;
@@ -551,6 +553,425 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   }
 }
 
+// ------------------------------------------------- dk, dv: 64 keys per wave (D = 128)
+// The main instance for D = 128.  Four waves of 64 keys each: every operand read from LDS (Q / dO
+// rows, their transposed blocks) now feeds two matrix instructions, which halves the LDS traffic
+// per product, the limit of the 32-keys-per-wave kernel above.  A wave then owns 256 accumulator
+// registers (dk and dv of 64 keys x 128 dims); they live in the AGPR half of the register file
+// for the whole kernel and only the matrix instructions touch them, while S / dP, which the
+// vector unit has to read, use ordinary VGPRs.  The compiler picks one register form for all
+// matrix instructions of a function, so the instructions are written out with their register
+// classes here; that leaves their dependency waits, which the compiler otherwise provides, to
+// this code (see the notes at lg_tie and in the step).
+// Accumulator I (0..15) is the fixed register block a[16 I : 16 I + 15]; the compiler only learns
+// that the statement overwrites those registers.  It must not use AGPRs for anything of its own
+// in this kernel (it has no reason to while nothing spills; tests/test_build_isa.py checks the
+// generated code).  zero clears the block through the matrix pipe (0 * 0 + 0); get copies it to
+// 16 floats once the last matrix instruction has certainly finished.
+template <int I>
+struct LgAcc;
+#define LG_ACC_CLOBBER(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15) \
+  "a" #R0, "a" #R1, "a" #R2, "a" #R3, "a" #R4, "a" #R5, "a" #R6, "a" #R7, "a" #R8, "a" #R9, "a" #R10, "a" #R11, \
+      "a" #R12, "a" #R13, "a" #R14, "a" #R15
+#define LG_ACC(I, LO, HI, R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15) \
+  template <> \
+  struct LgAcc<I> { \
+    static __device__ __forceinline__ void fma(bf16x8_t a, bf16x8_t b) { \
+      asm volatile("v_mfma_f32_32x32x16_bf16 a[" #LO ":" #HI "], %0, %1, a[" #LO ":" #HI "]" ::"v"(a), "v"(b) \
+                   : LG_ACC_CLOBBER(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15)); \
+    } \
+    static __device__ __forceinline__ void zero(bf16x8_t z) { \
+      asm volatile("v_mfma_f32_32x32x16_bf16 a[" #LO ":" #HI "], %0, %0, 0" ::"v"(z) \
+                   : LG_ACC_CLOBBER(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15)); \
+    } \
+    static __device__ __forceinline__ void get(float* x) { \
+      asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\t" "v_accvgpr_read_b32 %1, a" #R1 "\n\t" "v_accvgpr_read_b32 %2, a" #R2 "\n\t" "v_accvgpr_read_b32 %3, a" #R3 "\n\t" "v_accvgpr_read_b32 %4, a" #R4 "\n\t" "v_accvgpr_read_b32 %5, a" #R5 "\n\t" "v_accvgpr_read_b32 %6, a" #R6 "\n\t" "v_accvgpr_read_b32 %7, a" #R7 "\n\t" "v_accvgpr_read_b32 %8, a" #R8 "\n\t" "v_accvgpr_read_b32 %9, a" #R9 "\n\t" "v_accvgpr_read_b32 %10, a" #R10 "\n\t" "v_accvgpr_read_b32 %11, a" #R11 "\n\t" "v_accvgpr_read_b32 %12, a" #R12 "\n\t" "v_accvgpr_read_b32 %13, a" #R13 "\n\t" "v_accvgpr_read_b32 %14, a" #R14 "\n\t" "v_accvgpr_read_b32 %15, a" #R15 "\n\t" \
+                   : "=v"(x[0]), "=v"(x[1]), "=v"(x[2]), "=v"(x[3]), "=v"(x[4]), "=v"(x[5]), "=v"(x[6]), "=v"(x[7]), "=v"(x[8]), "=v"(x[9]), "=v"(x[10]), "=v"(x[11]), "=v"(x[12]), "=v"(x[13]), "=v"(x[14]), "=v"(x[15])); \
+    } \
+  };
+LG_ACC(0, 0, 15, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15)
+LG_ACC(1, 16, 31, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31)
+LG_ACC(2, 32, 47, 32, 33, 34, 35, 36, 37, 38, 39, 40, 41, 42, 43, 44, 45, 46, 47)
+LG_ACC(3, 48, 63, 48, 49, 50, 51, 52, 53, 54, 55, 56, 57, 58, 59, 60, 61, 62, 63)
+LG_ACC(4, 64, 79, 64, 65, 66, 67, 68, 69, 70, 71, 72, 73, 74, 75, 76, 77, 78, 79)
+LG_ACC(5, 80, 95, 80, 81, 82, 83, 84, 85, 86, 87, 88, 89, 90, 91, 92, 93, 94, 95)
+LG_ACC(6, 96, 111, 96, 97, 98, 99, 100, 101, 102, 103, 104, 105, 106, 107, 108, 109, 110, 111)
+LG_ACC(7, 112, 127, 112, 113, 114, 115, 116, 117, 118, 119, 120, 121, 122, 123, 124, 125, 126, 127)
+LG_ACC(8, 128, 143, 128, 129, 130, 131, 132, 133, 134, 135, 136, 137, 138, 139, 140, 141, 142, 143)
+LG_ACC(9, 144, 159, 144, 145, 146, 147, 148, 149, 150, 151, 152, 153, 154, 155, 156, 157, 158, 159)
+LG_ACC(10, 160, 175, 160, 161, 162, 163, 164, 165, 166, 167, 168, 169, 170, 171, 172, 173, 174, 175)
+LG_ACC(11, 176, 191, 176, 177, 178, 179, 180, 181, 182, 183, 184, 185, 186, 187, 188, 189, 190, 191)
+LG_ACC(12, 192, 207, 192, 193, 194, 195, 196, 197, 198, 199, 200, 201, 202, 203, 204, 205, 206, 207)
+LG_ACC(13, 208, 223, 208, 209, 210, 211, 212, 213, 214, 215, 216, 217, 218, 219, 220, 221, 222, 223)
+LG_ACC(14, 224, 239, 224, 225, 226, 227, 228, 229, 230, 231, 232, 233, 234, 235, 236, 237, 238, 239)
+LG_ACC(15, 240, 255, 240, 241, 242, 243, 244, 245, 246, 247, 248, 249, 250, 251, 252, 253, 254, 255)
+#undef LG_ACC
+#define LG_ACC_CASES(OP)                                                                                   \
+  switch (i) {                                                                                             \
+    case 0: OP(0); break; case 1: OP(1); break; case 2: OP(2); break; case 3: OP(3); break;                \
+    case 4: OP(4); break; case 5: OP(5); break; case 6: OP(6); break; case 7: OP(7); break;                \
+    case 8: OP(8); break; case 9: OP(9); break; case 10: OP(10); break; case 11: OP(11); break;            \
+    case 12: OP(12); break; case 13: OP(13); break; case 14: OP(14); break; default: OP(15); break;        \
+  }
+// i is a compile-time constant at every call (fully unrolled loops): the switch folds away
+__device__ __forceinline__ void lg_acc_fma(int i, bf16x8_t a, bf16x8_t b) {
+#define LG_OP(I) LgAcc<I>::fma(a, b)
+  LG_ACC_CASES(LG_OP)
+#undef LG_OP
+}
+__device__ __forceinline__ void lg_acc_zero(int i, bf16x8_t z) {
+#define LG_OP(I) LgAcc<I>::zero(z)
+  LG_ACC_CASES(LG_OP)
+#undef LG_OP
+}
+__device__ __forceinline__ void lg_acc_get(int i, float* x) {
+#define LG_OP(I) LgAcc<I>::get(x)
+  LG_ACC_CASES(LG_OP)
+#undef LG_OP
+}
+__device__ __forceinline__ void lg_mfma_v(f32x16_t& c, bf16x8_t a, bf16x8_t b) {  // accumulate in VGPRs
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void lg_mfma_v0(f32x16_t& c, bf16x8_t a, bf16x8_t b) {  // c = a b
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+}
+// Program-order anchor without an instruction: everything that reads x or y is placed after this
+// point, everything that wrote them before it.  A vector instruction may read a matrix result
+// only ~20 issue slots after the matrix instruction was issued; the anchors are set where at
+// least four later matrix instructions (32 slots) lie in between.
+__device__ __forceinline__ void lg_tie(f32x16_t& x, f32x16_t& y) { asm volatile("" : "+v"(x), "+v"(y)); }
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int... I, typename F>
+__device__ __forceinline__ void lg_static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void lg_static_for(F&& f) {
+  lg_static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+template <bool TOKEN>
+__global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
+    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group,
+    const float* __restrict__ part_dk, const float* __restrict__ part_dv, int ncol) {
+  LgMask m = m_in;
+  if (TOKEN) {
+    m.b = 1;
+    m.stride = 0;
+    m.bshift = 0;
+    m.smask = -1;
+    m.sb = m.sink;
+    m.wb = m.window;
+  }
+  constexpr int D = 128;
+  using T = LgSwzTile<D>;
+  constexpr int NT = 256;
+  using Dma = LgDma<D, NT>;
+  constexpr int TQ = LG_BF16_BTQ, TK = LG_BF16_BTK;
+  static_assert(TQ == 64 && TK == 256, "64 query rows per step, 4 waves x 64 keys");
+  constexpr int DC = D / 16, DB = D / 32;
+  constexpr int VRES = 4 * T::BYTES;                 // the workgroup's 256 V rows
+  constexpr int OFF_G = T::BYTES, OFF_L = 2 * T::BYTES;
+  constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, lse * log2(e) | Delta (2 x 64 floats)
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[VRES + 2 * STAGE];
+
+  const int G = Hq / Hkv;
+  const int N = m.N;
+  const float sl2 = scale * LOG2E;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, g = lane >> 5;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  // work item: as in the kernel above
+  int bh, kt;
+  if (ncol > 0) {
+    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (L >= total) return;
+    bh = L / nkt;
+    kt = L % nkt;
+  } else {
+    const int nbh = total / nkt;
+    if ((int)blockIdx.x < nbh) {
+      bh = blockIdx.x;
+      kt = 0;
+    } else {
+      const int idx = blockIdx.x - nbh;
+      const int L = (idx % 8) * per_xcd + idx / 8;
+      if (nkt == 1 || L >= total - nbh) return;
+      bh = L / (nkt - 1);
+      kt = 1 + L % (nkt - 1);
+    }
+  }
+  const int b = bh / Hkv, hk = bh % Hkv;
+  const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
+  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const int kw0 = k0 + wave_s * 64;  // this wave's 64 keys: lane n holds keys kw0 + n and kw0 + 32 + n
+  const int j = kw0 + n;
+
+  bf16x8_t kf[2][DC];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int jk = min(j + 32 * kb, N - 1);
+#pragma unroll
+    for (int dc = 0; dc < DC; ++dc)
+      kf[kb][dc] = lg_as_bf16x8(*reinterpret_cast<const uint4*>(k + kbase + (size_t)jk * D + dc * 16 + g * 8));
+  }
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int dc = 0; dc < DC; ++dc) asm volatile("" ::"v"(kf[kb][dc]));
+
+  // accumulators: dk of key block kb, dim block db = block kb * 4 + db; dv = block 8 + kb * 4 + db
+  const bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+#pragma unroll
+  for (int i = 0; i < 16; ++i) lg_acc_zero(i, zero8);
+
+  int lo, hi;
+  const int hq0 = hk * G;
+  if (ncol > 0) {  // the window part; the column part is the COLUMN instance's
+    lo = k0 / TQ;
+    hi = lg_qtile_window_hi(m, k1, TQ);
+  } else {
+    lg_qtile_range(m, k0, k1, TQ, &lo, &hi);
+  }
+  const int per_head = hi - lo + 1;
+  const int steps = per_head * G;
+
+  Dma dma;
+  dma.init(tid);
+  LgSwzReader<D> rd;
+  rd.init(n, g);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)LG_LDS_PTR(unsigned char, smem);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const int r0 = k0 + 64 * x;
+    const int rc = min(r0, N - 1);  // a tile wholly past the end repeats the last row
+    dma.issue(v + kbase + (size_t)rc * D, r0 < N ? N - r0 : 1, lds0 + x * T::BYTES);
+  }
+  const int voff = wave * T::BYTES;  // this wave's 64 V rows
+
+  auto issue_step = [&](int hq, int u, int buf) {
+    const int q0 = u * TQ;
+    const size_t row0 = (size_t)(b * Hq + hq) * N;
+    const uint32_t st = lds0 + VRES + buf * STAGE;
+    if (wave < 2) {  // wave 0: lse * log2(e) rows, wave 1: Delta rows (64 floats each)
+      const float* src = (wave == 0 ? lse2 : delta) + row0 + min(q0 + lane, N - 1);
+      lg_dma_f32x64(src, st + OFF_L + wave * 256);
+    }
+    dma.issue(q + (row0 + q0) * D, N - q0, st);
+    dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
+  };
+
+  const int u0 = lo + (per_head - lo % per_head) % per_head;  // rotated walk, as above
+  int hq_i = hq0, u_i = u0;
+  int u_c = u0;
+  int left_i = per_head;
+  issue_step(hq_i, u_i, 0);
+  for (int st = 0; st < steps; ++st) {
+    const int buf = st & 1;
+#ifndef LG_WIDE_NOWAIT
+    LG_WAIT_VMCNT(0);
+#endif
+    __syncthreads();  // step st landed for everyone; everyone is done with step st-1
+    if (st + 1 < steps) {
+      u_i = (u_i == hi) ? lo : u_i + 1;
+      if (--left_i == 0) {
+        left_i = per_head;
+        u_i = u0;
+        ++hq_i;
+      }
+      issue_step(hq_i, u_i, buf ^ 1);
+    }
+    const int q0 = u_c * TQ;
+    u_c = (u_c == hi) ? lo : u_c + 1;
+    const int q1 = min(q0 + TQ - 1, N - 1);
+    const int kind = lg_tile_kind(m, q0, q1, kw0, kw0 + 63);
+    if (kind == LG_TILE_DEAD) continue;
+    const bool full = kind == LG_TILE_FULL && q0 + TQ <= N;
+    const int sq = VRES + buf * STAGE, sg = sq + OFF_G;
+    const float* sL = reinterpret_cast<const float*>(smem + sq + OFF_L);
+    // bit 16 qb + r of bits[kb]: pair (row of register r of query block qb, key j + 32 kb) is live
+    uint32_t bits[2] = {~0u, ~0u};
+    if (!full) {
+      if (TOKEN) {
+        // in tile coordinates (row = q0 + 4g + c): key j + 32 kb is seen by the rows c with
+        // lo_c <= c < lo_c + window (no upper end for a sink key), below n_c
+        const int n_c = N - q0 - 4 * g;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          const int lo_c = j + 32 * kb - q0 - 4 * g;
+          const unsigned w_eff = j + 32 * kb < m.sink ? 0x7fffffffu : (unsigned)m.window;
+          uint32_t w = 0;
+#pragma unroll 1
+          for (int r = 0; r < 32; ++r) {  // partial tiles are few: a plain loop keeps the code small
+            const int c = 32 * (r >> 4) + lg_crow(r & 15, 0);
+            w |= (uint32_t)((unsigned)(c - lo_c) < w_eff && c < n_c) << r;
+          }
+          bits[kb] = w;
+        }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          uint32_t w = 0;
+#pragma unroll 1
+          for (int r = 0; r < 32; ++r) {
+            const int i = q0 + (r >> 4) * 32 + lg_crow(r & 15, g);
+            w |= (uint32_t)(i < N && lg_live(m, i, j + 32 * kb)) << r;
+          }
+          bits[kb] = w;
+        }
+      }
+    }
+    auto dead = [&](int kb, int qb, int r) -> bool { return !((bits[kb] >> (qb * 16 + r)) & 1); };
+
+    // One step = two 32-row query blocks (q) = 128 matrix instructions m, in pairs (units) that
+    // share one operand read from LDS (one instruction for each key block); per block, m - 64 q:
+    //    0..15  S  = Q K^T      16..31  dP = dO V^T      32..47  C: dV^T += dO^T P
+    //   48..63  D: dK^T += Q^T dS
+    // The instructions keep this order.  The LDS operand of unit u + DIST is requested before unit
+    // u runs.  The vector work is cut into pieces of two elements (five instructions) and each
+    // piece is placed after one matrix instruction, in whose shadow it then executes:
+    //   22..29  P of rows h = 0 (both key blocks; S is final six instructions after its last one)
+    //   32..39  P of rows h = 1           (C needs P of h = 0 from 32 on, of h = 1 from 40 on)
+    //   40..47  dS of rows h = 0          (dP is final from 38 on; D needs dS of h = 0 from 48 on)
+    //   48..55  dS of rows h = 1          (all vector work of a block ends before the next block's S)
+    // The per-row values (lse, Delta) of two pieces are requested two instructions ahead.
+    f32x16_t sc[2], dp[2];
+    uint32_t wP[2][2][4], wD[2][2][4];  // P / dS rounded to bf16, [key block][h][pair]
+#ifndef LG_WIDE_DIST
+#define LG_WIDE_DIST 2
+#endif
+    constexpr int DIST = LG_WIDE_DIST, NSL = DIST + 1;
+    bf16x8_t ra[NSL], rv0[NSL], rv1[NSL];
+    float4 lrow[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};  // by pair of pieces
+    auto reads = [&](int u) {  // u = 0..63: unit (m / 2) of the step
+      const int sl = u % NSL, c = u & 7, q = u >> 5, ph = (u >> 3) & 3;
+      if (ph == 0) {
+        ra[sl] = rd.read_rows(smem, sq, q, c);
+      } else if (ph == 1) {
+        ra[sl] = rd.read_rows(smem, sg, q, c);
+        rv0[sl] = rd.read_rows(smem, voff, 0, c);
+        rv1[sl] = rd.read_rows(smem, voff, 1, c);
+      } else if (ph == 2) {
+        ra[sl] = rd.read_cols(smem, sg, c & 3, 2 * q + (c >> 2));  // dO^T, rows 32 q + 16 h ..
+      } else {
+        ra[sl] = rd.read_cols(smem, sq, c & 3, 2 * q + (c >> 2));  // Q^T
+      }
+    };
+    // piece i (0..3) of (key block kb, half h): elements r = 8 h + 2 i, + 1; rows 8 (2 h + i / 2) + 4 g + 2 (i % 2), + 1
+    auto row_pre = [&](const float* base, int q, int h, int i) {  // for pieces i (even) and i + 1
+      lrow[(i >> 1) & 1] = *reinterpret_cast<const float4*>(base + q * 32 + 8 * (2 * h + (i >> 1)) + 4 * g);
+    };
+    auto sm_piece = [&](bool masked, int q, int kb, int h, int i) {
+      const float4 lr = lrow[(i >> 1) & 1];
+      const float l0 = (i & 1) ? lr.z : lr.x, l1 = (i & 1) ? lr.w : lr.y;
+      const int r = 8 * h + 2 * i;
+      float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], sl2, -l0));
+      float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][r + 1], sl2, -l1));
+      if (masked) {
+        if (dead(kb, q, r)) p0 = 0.f;
+        if (dead(kb, q, r + 1)) p1 = 0.f;
+      }
+      sc[kb][r] = p0;
+      sc[kb][r + 1] = p1;
+      wP[kb][h][i] = lg_pack_bf16(p0, p1);
+    };
+    auto ds_piece = [&](int kb, int h, int i) {
+      const float4 lr = lrow[(i >> 1) & 1];
+      const float d0 = (i & 1) ? lr.z : lr.x, d1 = (i & 1) ? lr.w : lr.y;
+      const int r = 8 * h + 2 * i;
+      wD[kb][h][i] = lg_pack_bf16(sc[kb][r] * (dp[kb][r] - d0), sc[kb][r + 1] * (dp[kb][r + 1] - d1));
+    };
+    auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
+
+    // two copies of the step: tiles that are live throughout skip the mask tests
+    auto run_step = [&](auto MASKED) {
+    constexpr bool masked = decltype(MASKED)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    lg_static_for<DIST>([&](auto U) { reads(decltype(U)::value); });
+    lg_static_for<128>([&](auto M) {
+      constexpr int m = decltype(M)::value;
+      constexpr int u = m >> 1, kb = m & 1, sl = u % NSL, c = u & 7, q = m >> 6, mm = m & 63, ph = mm >> 4;
+      if (kb == 0 && u + DIST < 64) reads(u + DIST);
+      if (ph == 0) {
+        if (c == 0) lg_mfma_v0(sc[kb], ra[sl], kf[kb][c]);
+        else lg_mfma_v(sc[kb], ra[sl], kf[kb][c]);
+      } else if (ph == 1) {
+        if (c == 0) lg_mfma_v0(dp[kb], ra[sl], kb ? rv1[sl] : rv0[sl]);
+        else lg_mfma_v(dp[kb], ra[sl], kb ? rv1[sl] : rv0[sl]);
+      } else if (ph == 2) {
+        lg_acc_fma(8 + 4 * kb + (c & 3), ra[sl], bop(wP[kb][c >> 2]));
+      } else {
+        lg_acc_fma(4 * kb + (c & 3), ra[sl], bop(wD[kb][c >> 2]));
+      }
+      if (mm == 21) lg_tie(sc[0], sc[1]);
+      if (mm == 37) lg_tie(dp[0], dp[1]);
+      __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
+#ifndef LG_WIDE_NOVALU
+      // pieces: P h0 at 22..29, P h1 at 32..39, dS h0 at 40..47, dS h1 at 48..55; key block = bit 2
+      if (mm >= 22 && mm < 30) sm_piece(masked, q, ((mm - 22) >> 2) & 1, 0, (mm - 22) & 3);
+      if (mm >= 32 && mm < 40) sm_piece(masked, q, ((mm - 32) >> 2) & 1, 1, (mm - 32) & 3);
+      if (mm >= 40 && mm < 48) ds_piece(((mm - 40) >> 2) & 1, 0, (mm - 40) & 3);
+      if (mm >= 48 && mm < 56) ds_piece(((mm - 48) >> 2) & 1, 1, (mm - 48) & 3);
+      // per-row values for the pieces at mm + 2, mm + 3 (when mm + 2 starts a pair of pieces)
+      if (mm >= 20 && mm < 28 && ((mm - 20) & 1) == 0) row_pre(sL, q, 0, (mm - 20) & 3);
+      if (mm >= 30 && mm < 38 && ((mm - 30) & 1) == 0) row_pre(sL, q, 1, (mm - 30) & 3);
+      if (mm >= 38 && mm < 46 && ((mm - 38) & 1) == 0) row_pre(sL + 64, q, 0, (mm - 38) & 3);
+      if (mm >= 46 && mm < 54 && ((mm - 46) & 1) == 0) row_pre(sL + 64, q, 1, (mm - 46) & 3);
+#else
+      if (m == 0)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) (&wP[0][0][0])[x] = (&wD[0][0][0])[x] = 0x3c003c00u;
+#endif
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    };
+    if (full) run_step(std::false_type{});
+    else run_step(std::true_type{});
+  }
+
+  // the last matrix results must have landed before the blocks are copied out
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  const int cid = (ncol > 0 && kw0 < N) ? col_of_group[kw0 >> 6] : -1;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int jj = j + 32 * kb;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      float akv[16], avv[16];
+      lg_acc_get(kb * 4 + db, akv);
+      lg_acc_get(8 + kb * 4 + db, avv);
+      if (jj < N)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        float a4[4], v4[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          a4[t] = akv[4 * r4 + t];
+          v4[t] = avv[4 * r4 + t];
+        }
+        if (cid >= 0) {  // fold in the column part's partial sums
+          const size_t prow = (((size_t)bh * ncol + cid) * 64 + kb * 32 + n) * D;
+          const float4 pk = *reinterpret_cast<const float4*>(part_dk + prow + db * 32 + 8 * r4 + 4 * g);
+          const float4 pv = *reinterpret_cast<const float4*>(part_dv + prow + db * 32 + 8 * r4 + 4 * g);
+          a4[0] += pk.x; a4[1] += pk.y; a4[2] += pk.z; a4[3] += pk.w;
+          v4[0] += pv.x; v4[1] += pv.y; v4[2] += pv.z; v4[3] += pv.w;
+        }
+        uint2 w;
+        w.x = lg_pack_bf16(a4[0] * scale, a4[1] * scale);
+        w.y = lg_pack_bf16(a4[2] * scale, a4[3] * scale);
+        *reinterpret_cast<uint2*>(dk + kbase + (size_t)jj * D + db * 32 + 8 * r4 + 4 * g) = w;
+        w.x = lg_pack_bf16(v4[0], v4[1]);
+        w.y = lg_pack_bf16(v4[2], v4[3]);
+        *reinterpret_cast<uint2*>(dv + kbase + (size_t)jj * D + db * 32 + 8 * r4 + 4 * g) = w;
+      }
+    }
+  }
+}
+
 }  // namespace
 
 // Workspace of the bf16 backward after Delta: two int tables of nkt entries, then the float32
@@ -677,7 +1098,18 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const dim3 grid_main(cl.ncol > 0 ? per_xcd * 8 : nbh + per_xcd_main * 8);
     {
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
-      LG_DKDV_BOTH(false, grid_main);
+      if (sh.D == 128) {
+        if (token)
+          dkdv_wide_bf16_kernel<true><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,
+                                                                (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
+                                                                per_xcd, col_of_group, pdk, pdv, cl.ncol);
+        else
+          dkdv_wide_bf16_kernel<false><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,
+                                                                 (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
+                                                                 per_xcd, col_of_group, pdk, pdv, cl.ncol);
+      } else {
+        LG_DKDV_BOTH(false, grid_main);
+      }
     }
 #undef LG_DKDV_BOTH
 #undef LG_DKDV_LAUNCH
