@@ -43,7 +43,7 @@ constexpr float LOG2E = 1.44269504088896340736f;
 template <int D, bool TOKEN>
 __global__ __launch_bounds__(512) void dq_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ ndelta,
     uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m_in, int nqt, int total, int per_xcd) {
   LgMask m = m_in;
   if (TOKEN) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
   }
   const float sl2 = scale * LOG2E;
   float lse2 = lse[(size_t)(b * Hq + hq) * N + iq] * LOG2E;
-  float di = delta[(size_t)(b * Hq + hq) * N + iq];
+  float di = -ndelta[(size_t)(b * Hq + hq) * N + iq];  // the pre-pass stores -Delta
   // Touch everything loaded so far, so that the compiler's waits for these loads sit here and
   // not inside the tile loop (where they would drain the direct loads kept in flight).
 #pragma unroll
@@ -251,7 +251,7 @@ __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4) {
 template <int D, bool TOKEN, bool COLUMN>
 __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
+    const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
     int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
     float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   constexpr int HALF = 32 * T::ROW_BYTES;
   constexpr int VRES = 4 * T::BYTES;                 // the workgroup's 256 V rows
   constexpr int OFF_G = T::BYTES, OFF_L = 2 * T::BYTES;
-  constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, lse*log2e | Delta (2 x 64 floats)
+  constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, -lse / scale | -Delta (2 x 64 floats)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[VRES + 2 * STAGE];
 
   const int G = Hq / Hkv;
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const uint32_t st = lds0 + VRES + buf * STAGE;
     // the small per-row loads go first: anything the compiler makes them wait for must not
     // include the tile loads issued below
-    if (wave < 2) {  // wave 0: lse * log2(e) rows, wave 1: Delta rows (64 floats each)
-      const float* src = (wave == 0 ? lse2 : delta) + row0 + min(q0 + lane, N - 1);
+    if (wave < 2) {  // wave 0: -lse / scale rows, wave 1: -Delta rows (64 floats each)
+      const float* src = (wave == 0 ? nlse : ndelta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
     dma.issue(q + (row0 + q0) * D, N - q0, st);
@@ -457,23 +457,20 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
       float p[16];
       __builtin_amdgcn_sched_barrier(0);  // phases stay apart: bounds the operands held at once
       {
+        // the accumulator starts from -lse / scale of its rows (register r <-> row 8 (r / 4) + 4g + r % 4)
         f32x16_t sc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 l4 = *reinterpret_cast<const float4*>(sL + qb * 32 + 8 * r4 + 4 * g);
+          sc[4 * r4 + 0] = l4.x; sc[4 * r4 + 1] = l4.y; sc[4 * r4 + 2] = l4.z; sc[4 * r4 + 3] = l4.w;
+        }
 #pragma unroll
         for (int dc = 0; dc < DC; ++dc) sc = lg_mfma32(rd.read_rows(smem, sq, qb, dc), kf[dc], sc);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          // rows 8*r4 + 4g .. +3 of this 32-row block: their lse, 16 bytes
-          const float4 l4 = *reinterpret_cast<const float4*>(sL + qb * 32 + 8 * r4 + 4 * g);
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int r = 4 * r4 + t;
-            float pv = __builtin_amdgcn_exp2f(fmaf(sc[r], sl2, -lv[t]));
-            if (!full && dead(qb, r)) pv = 0.f;
-            p[r] = pv;
-          }
+        for (int r = 0; r < 16; ++r) {
+          float pv = __builtin_amdgcn_exp2f(sc[r] * sl2);
+          if (!full && dead(qb, r)) pv = 0.f;
+          p[r] = pv;
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -485,19 +482,17 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
       }
       __builtin_amdgcn_sched_barrier(0);
       {
-        f32x16_t dp;
+        f32x16_t dp;  // starts from -Delta of its rows
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 d4 = *reinterpret_cast<const float4*>(sL + 64 + qb * 32 + 8 * r4 + 4 * g);
+          dp[4 * r4 + 0] = d4.x; dp[4 * r4 + 1] = d4.y; dp[4 * r4 + 2] = d4.z; dp[4 * r4 + 3] = d4.w;
+        }
 #pragma unroll
         for (int dc = 0; dc < DC; ++dc)
           dp = lg_mfma32(rd.read_rows(smem, sg, qb, dc), rd.read_rows(smem, voff, 0, dc), dp);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const float4 d4 = *reinterpret_cast<const float4*>(sL + 64 + qb * 32 + 8 * r4 + 4 * g);
-          const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int t = 0; t < 4; ++t) p[4 * r4 + t] *= dp[4 * r4 + t] - dv4[t];  // p becomes dS
-        }
+        for (int r = 0; r < 16; ++r) p[r] *= dp[r];  // p becomes dS
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -632,8 +627,8 @@ __device__ __forceinline__ void lg_acc_get(int i, float* x) {
 __device__ __forceinline__ void lg_mfma_v(f32x16_t& c, bf16x8_t a, bf16x8_t b) {  // accumulate in VGPRs
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
-__device__ __forceinline__ void lg_mfma_v0(f32x16_t& c, bf16x8_t a, bf16x8_t b) {  // c = a b
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+__device__ __forceinline__ void lg_mfma_vi(f32x16_t& c, bf16x8_t a, bf16x8_t b, const f32x16_t& init) {  // c = a b + init
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(c) : "v"(a), "v"(b), "v"(init));
 }
 // Program-order anchor without an instruction: everything that reads x or y is placed after this
 // point, everything that wrote them before it.  A vector instruction may read a matrix result
@@ -654,7 +649,7 @@ __device__ __forceinline__ void lg_static_for(F&& f) {
 template <bool TOKEN>
 __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse2, const float* __restrict__ delta,
+    const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
     int nkt, int total, int per_xcd, const int* __restrict__ col_of_group,
     const float* __restrict__ part_dk, const float* __restrict__ part_dv, int ncol) {
@@ -676,7 +671,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   constexpr int DC = D / 16, DB = D / 32;
   constexpr int VRES = 4 * T::BYTES;                 // the workgroup's 256 V rows
   constexpr int OFF_G = T::BYTES, OFF_L = 2 * T::BYTES;
-  constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, lse * log2(e) | Delta (2 x 64 floats)
+  constexpr int STAGE = 2 * T::BYTES + 1024;         // Q tile, dO tile, -lse / scale | -Delta (2 x 64 floats)
   __shared__ __attribute__((aligned(1024))) unsigned char smem[VRES + 2 * STAGE];
 
   const int G = Hq / Hkv;
@@ -757,8 +752,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     const int q0 = u * TQ;
     const size_t row0 = (size_t)(b * Hq + hq) * N;
     const uint32_t st = lds0 + VRES + buf * STAGE;
-    if (wave < 2) {  // wave 0: lse * log2(e) rows, wave 1: Delta rows (64 floats each)
-      const float* src = (wave == 0 ? lse2 : delta) + row0 + min(q0 + lane, N - 1);
+    if (wave < 2) {  // wave 0: -lse / scale rows, wave 1: -Delta rows (64 floats each)
+      const float* src = (wave == 0 ? nlse : ndelta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
     dma.issue(q + (row0 + q0) * D, N - q0, st);
@@ -838,7 +833,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     //   32..39  P of rows h = 1           (C needs P of h = 0 from 32 on, of h = 1 from 40 on)
     //   40..47  dS of rows h = 0          (dP is final from 38 on; D needs dS of h = 0 from 48 on)
     //   48..55  dS of rows h = 1          (all vector work of a block ends before the next block's S)
-    // The per-row values (lse, Delta) of two pieces are requested two instructions ahead.
+    // S and dP start from the per-row values -lse / scale and -Delta (16 rows per lane, read from
+    // LDS eight instructions before the chain starts), so P = exp2(c S') and dS = P dP'.
     f32x16_t sc[2], dp[2];
     uint32_t wP[2][2][4], wD[2][2][4];  // P / dS rounded to bf16, [key block][h][pair]
 #ifndef LG_WIDE_DIST
@@ -846,7 +842,14 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 #endif
     constexpr int DIST = LG_WIDE_DIST, NSL = DIST + 1;
     bf16x8_t ra[NSL], rv0[NSL], rv1[NSL];
-    float4 lrow[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};  // by pair of pieces
+    f32x16_t rowinit;
+    auto row_init = [&](const float* base, int q) {  // register r <-> row 8 (r / 4) + 4g + r % 4 of block q
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const float4 x = *reinterpret_cast<const float4*>(base + q * 32 + 8 * r4 + 4 * g);
+        rowinit[4 * r4 + 0] = x.x; rowinit[4 * r4 + 1] = x.y; rowinit[4 * r4 + 2] = x.z; rowinit[4 * r4 + 3] = x.w;
+      }
+    };
     auto reads = [&](int u) {  // u = 0..63: unit (m / 2) of the step
       const int sl = u % NSL, c = u & 7, q = u >> 5, ph = (u >> 3) & 3;
       if (ph == 0) {
@@ -861,16 +864,11 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
         ra[sl] = rd.read_cols(smem, sq, c & 3, 2 * q + (c >> 2));  // Q^T
       }
     };
-    // piece i (0..3) of (key block kb, half h): elements r = 8 h + 2 i, + 1; rows 8 (2 h + i / 2) + 4 g + 2 (i % 2), + 1
-    auto row_pre = [&](const float* base, int q, int h, int i) {  // for pieces i (even) and i + 1
-      lrow[(i >> 1) & 1] = *reinterpret_cast<const float4*>(base + q * 32 + 8 * (2 * h + (i >> 1)) + 4 * g);
-    };
+    // piece i (0..3) of (key block kb, half h): elements r = 8 h + 2 i, + 1
     auto sm_piece = [&](bool masked, int q, int kb, int h, int i) {
-      const float4 lr = lrow[(i >> 1) & 1];
-      const float l0 = (i & 1) ? lr.z : lr.x, l1 = (i & 1) ? lr.w : lr.y;
       const int r = 8 * h + 2 * i;
-      float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], sl2, -l0));
-      float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][r + 1], sl2, -l1));
+      float p0 = __builtin_amdgcn_exp2f(sc[kb][r] * sl2);
+      float p1 = __builtin_amdgcn_exp2f(sc[kb][r + 1] * sl2);
       if (masked) {
         if (dead(kb, q, r)) p0 = 0.f;
         if (dead(kb, q, r + 1)) p1 = 0.f;
@@ -880,10 +878,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
       wP[kb][h][i] = lg_pack_bf16(p0, p1);
     };
     auto ds_piece = [&](int kb, int h, int i) {
-      const float4 lr = lrow[(i >> 1) & 1];
-      const float d0 = (i & 1) ? lr.z : lr.x, d1 = (i & 1) ? lr.w : lr.y;
       const int r = 8 * h + 2 * i;
-      wD[kb][h][i] = lg_pack_bf16(sc[kb][r] * (dp[kb][r] - d0), sc[kb][r + 1] * (dp[kb][r + 1] - d1));
+      wD[kb][h][i] = lg_pack_bf16(sc[kb][r] * dp[kb][r], sc[kb][r + 1] * dp[kb][r + 1]);
     };
     auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
 
@@ -891,16 +887,17 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     auto run_step = [&](auto MASKED) {
     constexpr bool masked = decltype(MASKED)::value;
     __builtin_amdgcn_sched_barrier(0);
+    row_init(sL, 0);
     lg_static_for<DIST>([&](auto U) { reads(decltype(U)::value); });
     lg_static_for<128>([&](auto M) {
       constexpr int m = decltype(M)::value;
       constexpr int u = m >> 1, kb = m & 1, sl = u % NSL, c = u & 7, q = m >> 6, mm = m & 63, ph = mm >> 4;
       if (kb == 0 && u + DIST < 64) reads(u + DIST);
       if (ph == 0) {
-        if (c == 0) lg_mfma_v0(sc[kb], ra[sl], kf[kb][c]);
+        if (c == 0) lg_mfma_vi(sc[kb], ra[sl], kf[kb][c], rowinit);
         else lg_mfma_v(sc[kb], ra[sl], kf[kb][c]);
       } else if (ph == 1) {
-        if (c == 0) lg_mfma_v0(dp[kb], ra[sl], kb ? rv1[sl] : rv0[sl]);
+        if (c == 0) lg_mfma_vi(dp[kb], ra[sl], kb ? rv1[sl] : rv0[sl], rowinit);
         else lg_mfma_v(dp[kb], ra[sl], kb ? rv1[sl] : rv0[sl]);
       } else if (ph == 2) {
         lg_acc_fma(8 + 4 * kb + (c & 3), ra[sl], bop(wP[kb][c >> 2]));
@@ -909,6 +906,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
       }
       if (mm == 21) lg_tie(sc[0], sc[1]);
       if (mm == 37) lg_tie(dp[0], dp[1]);
+      if (mm == 8) row_init(sL + 64, q);             // -Delta rows: dP starts at 16
+      if (m == 56) row_init(sL, 1);                  // -lse / scale rows of the second block
       __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
 #ifndef LG_WIDE_NOVALU
       // pieces: P h0 at 22..29, P h1 at 32..39, dS h0 at 40..47, dS h1 at 48..55; key block = bit 2
@@ -916,11 +915,6 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
       if (mm >= 32 && mm < 40) sm_piece(masked, q, ((mm - 32) >> 2) & 1, 1, (mm - 32) & 3);
       if (mm >= 40 && mm < 48) ds_piece(((mm - 40) >> 2) & 1, 0, (mm - 40) & 3);
       if (mm >= 48 && mm < 56) ds_piece(((mm - 48) >> 2) & 1, 1, (mm - 48) & 3);
-      // per-row values for the pieces at mm + 2, mm + 3 (when mm + 2 starts a pair of pieces)
-      if (mm >= 20 && mm < 28 && ((mm - 20) & 1) == 0) row_pre(sL, q, 0, (mm - 20) & 3);
-      if (mm >= 30 && mm < 38 && ((mm - 30) & 1) == 0) row_pre(sL, q, 1, (mm - 30) & 3);
-      if (mm >= 38 && mm < 46 && ((mm - 38) & 1) == 0) row_pre(sL + 64, q, 0, (mm - 38) & 3);
-      if (mm >= 46 && mm < 54 && ((mm - 46) & 1) == 0) row_pre(sL + 64, q, 1, (mm - 46) & 3);
 #else
       if (m == 0)
 #pragma unroll
@@ -1020,12 +1014,15 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
                               const float* lse, const void* dout, void* dq, void* dk, void* dv,
                               void* ws, const LgShape& sh, const LgMask& m, hipStream_t s,
                               hipEvent_t* ev) {
-  // workspace: Delta | lse * log2(e) | column tables and partial sums
+  // workspace: -Delta | -lse / scale | column tables and partial sums.  In this form the dk/dv
+  // kernels start the S and dP accumulators from them: S - lse / scale needs one multiply before
+  // exp2, and dP - Delta comes out of the matrix pipe directly.
   const size_t row_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
-  float* delta = (float*)ws;
-  float* lse2 = (float*)((char*)ws + row_bytes);
+  float* ndelta = (float*)ws;
+  float* nlse = (float*)((char*)ws + row_bytes);
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = lg_launch_delta(dout, out, delta, lse, lse2, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
+  hipError_t e = lg_launch_delta(dout, out, ndelta, lse, nlse, -1.f, -1.f / sh.scale,
+                                 (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const uint16_t* uq = (const uint16_t*)q;
@@ -1040,7 +1037,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const int total = (int)tl, per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8);
 #define LG_DQ_LAUNCH(DD, TT)                                                                        \
-  dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, delta, (uint16_t*)dq, sh.Hq, sh.Hkv, \
+  dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv, \
                                               sh.scale, m, nqt, total, per_xcd)
     if (sh.D == 64) {
       if (token) LG_DQ_LAUNCH(64, true);
@@ -1066,7 +1063,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     float* pdk = (float*)((char*)ws + cl.pdk_off);
     float* pdv = (float*)((char*)ws + cl.pdv_off);
 #define LG_DKDV_LAUNCH(DD, TT, CC, GRID)                                                                  \
-  dkdv_bf16_kernel<DD, TT, CC><<<GRID, 512, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,              \
+  dkdv_bf16_kernel<DD, TT, CC><<<GRID, 512, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,             \
                                                     (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,  \
                                                     per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol,     \
                                                     cl.nchunk)
@@ -1100,11 +1097,11 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
       if (sh.D == 128) {
         if (token)
-          dkdv_wide_bf16_kernel<true><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,
+          dkdv_wide_bf16_kernel<true><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,
                                                                 (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
                                                                 per_xcd, col_of_group, pdk, pdv, cl.ncol);
         else
-          dkdv_wide_bf16_kernel<false><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, lse2, delta, (uint16_t*)dk,
+          dkdv_wide_bf16_kernel<false><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,
                                                                  (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
                                                                  per_xcd, col_of_group, pdk, pdv, cl.ncol);
       } else {

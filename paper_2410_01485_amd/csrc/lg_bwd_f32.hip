@@ -40,12 +40,13 @@ __device__ __forceinline__ float dot16(const __hip_bfloat16* a, const __hip_bflo
   return s;
 }
 
-// One row per LPR = D*sizeof(T)/16 lanes; rows = B*Hq*N.  lse2 (optional): lse * log2(e), the
-// form the bf16 dk/dv kernel feeds straight into exp2.
+// One row per LPR = D*sizeof(T)/16 lanes; rows = B*Hq*N.  delta = dsign * <dout, out>;
+// lse2 (optional) = lse * lscale.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ dout, const T* __restrict__ out,
                                                     float* __restrict__ delta, const float* __restrict__ lse,
-                                                    float* __restrict__ lse2, long long rows) {
+                                                    float* __restrict__ lse2, float dsign, float lscale,
+                                                    long long rows) {
   constexpr int E = 16 / sizeof(T);
   constexpr int LPR = D / E;
   const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
@@ -55,8 +56,8 @@ __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ dout, 
 #pragma unroll
   for (int x = 1; x < LPR; x <<= 1) s += __shfl_xor(s, x);
   if (c == 0 && row < rows) {
-    delta[row] = s;
-    if (lse2) lse2[row] = lse[row] * 1.44269504088896340736f;
+    delta[row] = dsign * s;
+    if (lse2) lse2[row] = lse[row] * lscale;
   }
 }
 
@@ -218,14 +219,14 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const float* __restrict__
 
 template <typename T>
 hipError_t launch_delta_t(const void* dout, const void* out, float* delta, const float* lse, float* lse2,
-                          long long rows, int D, hipStream_t s) {
+                          float dsign, float lscale, long long rows, int D, hipStream_t s) {
   const int lpr = D * (int)sizeof(T) / 16;
   const int rpb = 256 / lpr;
   const unsigned grid = (unsigned)((rows + rpb - 1) / rpb);
   if (D == 64)
-    delta_kernel<T, 64><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, rows);
+    delta_kernel<T, 64><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows);
   else
-    delta_kernel<T, 128><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, rows);
+    delta_kernel<T, 128><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows);
   return hipGetLastError();
 }
 
@@ -233,14 +234,14 @@ hipError_t launch_delta_t(const void* dout, const void* out, float* delta, const
 
 // Delta pre-pass for either dtype (used by both backward paths).
 hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, const float* lse, float* lse2,
-                           long long rows, int D, int dtype, hipStream_t s) {
-  return dtype == LG_F32 ? launch_delta_t<float>(dout, out, delta, lse, lse2, rows, D, s)
-                         : launch_delta_t<__hip_bfloat16>(dout, out, delta, lse, lse2, rows, D, s);
+                           float dsign, float lscale, long long rows, int D, int dtype, hipStream_t s) {
+  return dtype == LG_F32 ? launch_delta_t<float>(dout, out, delta, lse, lse2, dsign, lscale, rows, D, s)
+                         : launch_delta_t<__hip_bfloat16>(dout, out, delta, lse, lse2, dsign, lscale, rows, D, s);
 }
 
 size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype) {
-  // Delta [B, Hq, N] float32, rounded up to 256 bytes; the bf16 path adds lse * log2(e) in the same
-  // shape and its column-tile area
+  // Delta [B, Hq, N] float32, rounded up to 256 bytes; the bf16 path adds a scaled copy of lse in the
+  // same shape and its column-tile area
   const size_t n = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
   return dtype == LG_BF16 ? lg_bwd_bf16_workspace_bytes(sh, m, 2 * n) : n;
 }
@@ -251,7 +252,7 @@ hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, con
                              hipEvent_t* ev) {
   float* delta = (float*)ws;
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = lg_launch_delta(dout, out, delta, nullptr, nullptr, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_F32, s);
+  hipError_t e = lg_launch_delta(dout, out, delta, nullptr, nullptr, 1.f, 0.f, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_F32, s);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 gq((sh.N + LG_F32_TQ - 1) / LG_F32_TQ, sh.Hq, sh.B);
