@@ -767,9 +767,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   issue_step(hq_i, u_i, 0);
   for (int st = 0; st < steps; ++st) {
     const int buf = st & 1;
-#ifndef LG_WIDE_NOWAIT
     LG_WAIT_VMCNT(0);
-#endif
     __syncthreads();  // step st landed for everyone; everyone is done with step st-1
     if (st + 1 < steps) {
       u_i = (u_i == hi) ? lo : u_i + 1;
@@ -837,10 +835,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     // LDS eight instructions before the chain starts), so P = exp2(c S') and dS = P dP'.
     f32x16_t sc[2], dp[2];
     uint32_t wP[2][2][4], wD[2][2][4];  // P / dS rounded to bf16, [key block][h][pair]
-#ifndef LG_WIDE_DIST
-#define LG_WIDE_DIST 2
-#endif
-    constexpr int DIST = LG_WIDE_DIST, NSL = DIST + 1;
+    constexpr int DIST = 2, NSL = DIST + 1;
     bf16x8_t ra[NSL], rv0[NSL], rv1[NSL];
     f32x16_t rowinit;
     auto row_init = [&](const float* base, int q) {  // register r <-> row 8 (r / 4) + 4g + r % 4 of block q
@@ -909,17 +904,11 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
       if (mm == 8) row_init(sL + 64, q);             // -Delta rows: dP starts at 16
       if (m == 56) row_init(sL, 1);                  // -lse / scale rows of the second block
       __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
-#ifndef LG_WIDE_NOVALU
       // pieces: P h0 at 22..29, P h1 at 32..39, dS h0 at 40..47, dS h1 at 48..55; key block = bit 2
       if (mm >= 22 && mm < 30) sm_piece(masked, q, ((mm - 22) >> 2) & 1, 0, (mm - 22) & 3);
       if (mm >= 32 && mm < 40) sm_piece(masked, q, ((mm - 32) >> 2) & 1, 1, (mm - 32) & 3);
       if (mm >= 40 && mm < 48) ds_piece(((mm - 40) >> 2) & 1, 0, (mm - 40) & 3);
       if (mm >= 48 && mm < 56) ds_piece(((mm - 48) >> 2) & 1, 1, (mm - 48) & 3);
-#else
-      if (m == 0)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) (&wP[0][0][0])[x] = (&wD[0][0][0])[x] = 0x3c003c00u;
-#endif
       __builtin_amdgcn_sched_barrier(0);
     });
     };
@@ -1095,7 +1084,9 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const dim3 grid_main(cl.ncol > 0 ? per_xcd * 8 : nbh + per_xcd_main * 8);
     {
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
-      if (sh.D == 128) {
+      // the 64-keys-per-wave kernel pays off once a key tile has a dozen or more query tiles
+      const int win_steps = (m.wb * m.b + LG_BF16_BTK) / LG_BF16_BTQ;
+      if (sh.D == 128 && win_steps >= 16) {
         if (token)
           dkdv_wide_bf16_kernel<true><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,
                                                                 (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
