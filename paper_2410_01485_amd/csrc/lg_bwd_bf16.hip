@@ -955,6 +955,297 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   }
 }
 
+// ------------------------------------------------- dq: 64 query rows per wave (D = 128)
+// Same idea as the wide dk/dv kernel: four waves of 64 query rows, so that every K / V operand
+// read from LDS feeds two matrix instructions.  The AGPR half of the register file holds the dq
+// accumulators (blocks 0..7 = a[0:127]: row block rb, dim block db -> block 4 rb + db) and the
+// wave's Q and dO fragments (a[128:255], four registers per 32 rows x 16 dims), which the matrix
+// instructions read as their second operand straight from there.
+template <int I>
+struct LgFrag;
+#define LG_FRAG(I, LO, HI, R0, R1, R2, R3)                                                                     \
+  template <>                                                                                                  \
+  struct LgFrag<I> {                                                                                           \
+    static __device__ __forceinline__ void set(uint4 v) {                                                      \
+      asm volatile("v_accvgpr_write_b32 a" #R0 ", %0\n\tv_accvgpr_write_b32 a" #R1 ", %1\n\t"                   \
+                   "v_accvgpr_write_b32 a" #R2 ", %2\n\tv_accvgpr_write_b32 a" #R3 ", %3" ::"v"(v.x),            \
+                   "v"(v.y), "v"(v.z), "v"(v.w)                                                                \
+                   : "a" #R0, "a" #R1, "a" #R2, "a" #R3);                                                      \
+    }                                                                                                          \
+    static __device__ __forceinline__ void fma(f32x16_t& c, bf16x8_t a) {                                      \
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #LO ":" #HI "], %0" : "+v"(c) : "v"(a));               \
+    }                                                                                                          \
+    static __device__ __forceinline__ void mul(f32x16_t& c, bf16x8_t a) {                                      \
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #LO ":" #HI "], 0" : "=&v"(c) : "v"(a));               \
+    }                                                                                                          \
+  };
+LG_FRAG(0, 128, 131, 128, 129, 130, 131)
+LG_FRAG(1, 132, 135, 132, 133, 134, 135)
+LG_FRAG(2, 136, 139, 136, 137, 138, 139)
+LG_FRAG(3, 140, 143, 140, 141, 142, 143)
+LG_FRAG(4, 144, 147, 144, 145, 146, 147)
+LG_FRAG(5, 148, 151, 148, 149, 150, 151)
+LG_FRAG(6, 152, 155, 152, 153, 154, 155)
+LG_FRAG(7, 156, 159, 156, 157, 158, 159)
+LG_FRAG(8, 160, 163, 160, 161, 162, 163)
+LG_FRAG(9, 164, 167, 164, 165, 166, 167)
+LG_FRAG(10, 168, 171, 168, 169, 170, 171)
+LG_FRAG(11, 172, 175, 172, 173, 174, 175)
+LG_FRAG(12, 176, 179, 176, 177, 178, 179)
+LG_FRAG(13, 180, 183, 180, 181, 182, 183)
+LG_FRAG(14, 184, 187, 184, 185, 186, 187)
+LG_FRAG(15, 188, 191, 188, 189, 190, 191)
+LG_FRAG(16, 192, 195, 192, 193, 194, 195)
+LG_FRAG(17, 196, 199, 196, 197, 198, 199)
+LG_FRAG(18, 200, 203, 200, 201, 202, 203)
+LG_FRAG(19, 204, 207, 204, 205, 206, 207)
+LG_FRAG(20, 208, 211, 208, 209, 210, 211)
+LG_FRAG(21, 212, 215, 212, 213, 214, 215)
+LG_FRAG(22, 216, 219, 216, 217, 218, 219)
+LG_FRAG(23, 220, 223, 220, 221, 222, 223)
+LG_FRAG(24, 224, 227, 224, 225, 226, 227)
+LG_FRAG(25, 228, 231, 228, 229, 230, 231)
+LG_FRAG(26, 232, 235, 232, 233, 234, 235)
+LG_FRAG(27, 236, 239, 236, 237, 238, 239)
+LG_FRAG(28, 240, 243, 240, 241, 242, 243)
+LG_FRAG(29, 244, 247, 244, 245, 246, 247)
+LG_FRAG(30, 248, 251, 248, 249, 250, 251)
+LG_FRAG(31, 252, 255, 252, 253, 254, 255)
+#undef LG_FRAG
+#define LG_FRAG_CASES(OP) \
+  switch (i) { case 0: OP(0); break; case 1: OP(1); break; case 2: OP(2); break; case 3: OP(3); break; case 4: OP(4); break; case 5: OP(5); break; case 6: OP(6); break; case 7: OP(7); break; case 8: OP(8); break; case 9: OP(9); break; case 10: OP(10); break; case 11: OP(11); break; case 12: OP(12); break; case 13: OP(13); break; case 14: OP(14); break; case 15: OP(15); break; case 16: OP(16); break; case 17: OP(17); break; case 18: OP(18); break; case 19: OP(19); break; case 20: OP(20); break; case 21: OP(21); break; case 22: OP(22); break; case 23: OP(23); break; case 24: OP(24); break; case 25: OP(25); break; case 26: OP(26); break; case 27: OP(27); break; case 28: OP(28); break; case 29: OP(29); break; case 30: OP(30); break; default: OP(31); break; }
+// i is a compile-time constant at every call: the switch folds away
+__device__ __forceinline__ void lg_frag_set(int i, uint4 v) {
+#define LG_OP(I) LgFrag<I>::set(v)
+  LG_FRAG_CASES(LG_OP)
+#undef LG_OP
+}
+// c = (first ? 0 : c) + a * fragment i
+__device__ __forceinline__ void lg_frag_mfma(int i, bool first, f32x16_t& c, bf16x8_t a) {
+#define LG_OP(I)                    \
+  do {                              \
+    if (first) LgFrag<I>::mul(c, a); \
+    else LgFrag<I>::fma(c, a);      \
+  } while (0)
+  LG_FRAG_CASES(LG_OP)
+#undef LG_OP
+}
+
+template <bool TOKEN>
+__global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ ndelta,
+    uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m_in, int nqt, int total, int per_xcd) {
+  LgMask m = m_in;
+  if (TOKEN) {
+    m.b = 1;
+    m.stride = 0;
+    m.bshift = 0;
+    m.smask = -1;
+    m.sb = m.sink;
+    m.wb = m.window;
+  }
+  constexpr int D = 128;
+  using T = LgSwzTile<D>;
+  constexpr int NT = 256, STAGES = 4;
+  using Dma = LgDma<D, NT>;
+  constexpr int TQ = LG_BF16_TQ, TK = LG_BF16_TK;
+  static_assert(TQ == 256 && TK == 64, "4 waves x 64 query rows, 64-key tiles");
+  constexpr int DC = D / 16, DB = D / 32;
+  constexpr int STAGE = 2 * T::BYTES;  // K tile + V tile
+  constexpr int LPT = 2 * Dma::CH;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[STAGES * STAGE];
+
+  const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (L >= total) return;
+  const int G = Hq / Hkv;
+  const int gq = L % G, rest = L / G;
+  const int qt = nqt - 1 - (rest % nqt);
+  const int bhk = rest / nqt;
+  const int b = bhk / Hkv, hk = bhk % Hkv;
+  const int hq = hk * G + gq;
+  const int N = m.N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, g = lane >> 5;
+  const int q0 = qt * TQ, q1 = min(q0 + TQ - 1, N - 1);
+  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int qw0 = min(q0 + wave_s * 64, N - 1), qw1 = min(q0 + wave_s * 64 + 63, N - 1);  // this wave's rows
+  const int i0 = q0 + wave * 64 + n;  // this lane's row of row block 0 (block 1: + 32)
+
+  // fragments: Q of (rb, dc) -> fragment 8 rb + dc, dO -> 16 + 8 rb + dc
+  float lse2[2], di[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int iq = min(i0 + 32 * rb, N - 1);
+#pragma unroll
+    for (int dc = 0; dc < DC; ++dc) {
+      lg_frag_set(8 * rb + dc, *reinterpret_cast<const uint4*>(q + qbase + (size_t)iq * D + dc * 16 + g * 8));
+      lg_frag_set(16 + 8 * rb + dc, *reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8));
+    }
+    lse2[rb] = lse[(size_t)(b * Hq + hq) * N + iq] * LOG2E;
+    di[rb] = ndelta[(size_t)(b * Hq + hq) * N + iq];  // -Delta
+  }
+  const float sl2 = scale * LOG2E;
+  asm volatile("" : "+v"(lse2[0]), "+v"(lse2[1]), "+v"(di[0]), "+v"(di[1]));
+  const bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+#pragma unroll
+  for (int x = 0; x < 8; ++x) lg_acc_zero(x, zero8);
+
+  Dma dma;
+  dma.init(tid);
+  LgSwzReader<D> rd;
+  rd.init(n, g);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)LG_LDS_PTR(unsigned char, smem);
+  const LgQSched qs = lg_qsched_init(m, q0, q1);
+  auto issue = [&](int t, int stage) {
+    const size_t off = (size_t)t * TK * D;
+    dma.issue(kh + off, N - t * TK, lds0 + stage * STAGE);
+    dma.issue(vh + off, N - t * TK, lds0 + stage * STAGE + T::BYTES);
+  };
+  const LgQWalk qw = lg_qwalk_init(qs);
+  auto next_tile = [&](int prev) -> int {
+    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    return lg_qsched_next(m, qs, prev);
+  };
+  int t = next_tile(-1);
+  int t_issue = t;
+  int ahead = 0;
+  for (; ahead < STAGES - 1 && t_issue >= 0; ++ahead) {
+    issue(t_issue, ahead);
+    t_issue = next_tile(t_issue);
+  }
+  int stage = 0;
+  while (t >= 0) {
+    if (ahead >= 3) LG_WAIT_VMCNT(2 * LPT);
+    else if (ahead == 2) LG_WAIT_VMCNT(LPT);
+    else LG_WAIT_VMCNT(0);
+    __syncthreads();  // tile t landed for everyone; everyone is done with tile t-1
+    if (t_issue >= 0) {
+      issue(t_issue, (stage + STAGES - 1) % STAGES);
+      t_issue = next_tile(t_issue);
+      ++ahead;
+    }
+    const int k0 = t * TK;
+    int kind = LG_TILE_FULL;
+    if (!lg_qsched_full(m, qs, t)) kind = lg_tile_kind(m, qw0, qw1, k0, k0 + TK - 1);
+    const int sk = stage * STAGE, sv = sk + T::BYTES;
+    --ahead;
+    t = next_tile(t);
+    stage = (stage + 1) % STAGES;
+    if (kind == LG_TILE_DEAD) continue;
+    // bit 16 kb + r of bits[rb]: pair (row i0 + 32 rb, key of register r of key block kb) is live
+    uint32_t bits[2] = {~0u, ~0u};
+    if (kind == LG_TILE_PARTIAL) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const int i = i0 + 32 * rb;
+        uint32_t w = 0;
+        if (TOKEN) {
+          // key = k0 + 4g + c: live if inside the window of row i, or a sink key not after i
+          const int hi = i - k0 - 4 * g, lo = hi - (m.window - 1), se = m.sink - k0 - 4 * g;
+#pragma unroll 1
+          for (int r = 0; r < 32; ++r) {
+            const int c = 32 * (r >> 4) + lg_crow(r & 15, 0);
+            w |= (uint32_t)((unsigned)(c - lo) < (unsigned)m.window || (c < se && c <= hi)) << r;
+          }
+        } else {
+#pragma unroll 1
+          for (int r = 0; r < 32; ++r) w |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
+        }
+        bits[rb] = w;
+      }
+    }
+    auto dead = [&](int rb, int kb, int r) -> bool { return !((bits[rb] >> (kb * 16 + r)) & 1); };
+
+    // One tile = 96 matrix instructions mi, in pairs (units) that share one operand read from LDS
+    // (one instruction for each 32-row block rb):
+    //    0..15  S^T(0) = K Q^T    16..31  dP^T(0) = V dO^T    32..47  S^T(1)    48..63  dP^T(1)
+    //   64..79  E(0): dQ^T += K^T dS^T(0)                     80..95  E(1)
+    // (0), (1): key block of the tile.  S / dP of the two key blocks use separate registers, so the
+    // vector work of key block 0 runs under the instructions of key block 1, two elements after
+    // each instruction:  P(0) 22..37,  dS(0) 38..53,  P(1) 54..69,  dS(1) 70..85 (rows h = 0 of
+    // both row blocks first: E(1) needs them from 80 on, h = 1 from 88 on).
+    f32x16_t sc[2][2], dp[2][2];   // [key block][row block]
+    uint32_t wD[2][2][2][4];       // dS rounded to bf16: [key block][row block][h][pair]
+    constexpr int DIST = 2, NSL = DIST + 1;
+    bf16x8_t ra[NSL];
+    auto reads = [&](int u) {  // u = 0..47: unit (mi / 2) of the tile
+      const int sl = u % NSL, c = u & 7, ph = u >> 3;
+      if (ph == 0 || ph == 2) ra[sl] = rd.read_rows(smem, sk, ph >> 1, c);
+      else if (ph == 1 || ph == 3) ra[sl] = rd.read_rows(smem, sv, ph >> 1, c);
+      else ra[sl] = rd.read_cols(smem, sk, c & 3, 2 * (ph - 4) + (c >> 2));
+    };
+    // piece x (0..15) of key block kb: row block (x / 4) % 2, h = x / 8, elements 8 h + 2 (x % 4), + 1
+    auto p_piece = [&](bool masked, int kb, int x) {
+      const int rb = (x >> 2) & 1, r = 8 * (x >> 3) + 2 * (x & 3);
+      float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kb][rb][r], sl2, -lse2[rb]));
+      float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kb][rb][r + 1], sl2, -lse2[rb]));
+      if (masked) {
+        if (dead(rb, kb, r)) p0 = 0.f;
+        if (dead(rb, kb, r + 1)) p1 = 0.f;
+      }
+      sc[kb][rb][r] = p0;
+      sc[kb][rb][r + 1] = p1;
+    };
+    auto ds_piece = [&](int kb, int x) {
+      const int rb = (x >> 2) & 1, h = x >> 3, r = 8 * h + 2 * (x & 3);
+      wD[kb][rb][h][x & 3] = lg_pack_bf16(sc[kb][rb][r] * (dp[kb][rb][r] + di[rb]),
+                                          sc[kb][rb][r + 1] * (dp[kb][rb][r + 1] + di[rb]));
+    };
+    auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
+
+    auto run_tile = [&](auto MASKED) {
+      constexpr bool masked = decltype(MASKED)::value;
+      __builtin_amdgcn_sched_barrier(0);
+      lg_static_for<DIST>([&](auto U) { reads(decltype(U)::value); });
+      lg_static_for<96>([&](auto M) {
+        constexpr int mi = decltype(M)::value;
+        constexpr int u = mi >> 1, rb = mi & 1, sl = u % NSL, c = u & 7, ph = u >> 3;
+        if (rb == 0 && u + DIST < 48) reads(u + DIST);
+        if (ph == 0 || ph == 2) lg_frag_mfma(8 * rb + c, c == 0, sc[ph >> 1][rb], ra[sl]);
+        else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, c == 0, dp[ph >> 1][rb], ra[sl]);
+        else lg_acc_fma(4 * rb + (c & 3), ra[sl], bop(wD[ph - 4][rb][c >> 2]));
+        // S / dP are final six matrix instructions after their last one
+        if (mi == 21) lg_tie(sc[0][0], sc[0][1]);
+        if (mi == 37) lg_tie(dp[0][0], dp[0][1]);
+        if (mi == 53) lg_tie(sc[1][0], sc[1][1]);
+        if (mi == 69) lg_tie(dp[1][0], dp[1][1]);
+        __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
+        if (mi >= 22 && mi < 38) p_piece(masked, 0, mi - 22);
+        if (mi >= 38 && mi < 54) ds_piece(0, mi - 38);
+        if (mi >= 54 && mi < 70) p_piece(masked, 1, mi - 54);
+        if (mi >= 70 && mi < 86) ds_piece(1, mi - 70);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    if (kind == LG_TILE_FULL) run_tile(std::false_type{});
+    else run_tile(std::true_type{});
+  }
+
+  // the last matrix results must have landed before the blocks are copied out
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int i = i0 + 32 * rb;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      float a[16];
+      lg_acc_get(4 * rb + db, a);
+      if (i < N)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          uint2 w;
+          w.x = lg_pack_bf16(a[4 * r4 + 0] * scale, a[4 * r4 + 1] * scale);
+          w.y = lg_pack_bf16(a[4 * r4 + 2] * scale, a[4 * r4 + 3] * scale);
+          *reinterpret_cast<uint2*>(dq + qbase + (size_t)i * D + db * 32 + 8 * r4 + 4 * g) = w;
+        }
+    }
+  }
+}
+
 }  // namespace
 
 // Workspace of the bf16 backward after Delta: two int tables of nkt entries, then the float32
@@ -1031,9 +1322,16 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (sh.D == 64) {
       if (token) LG_DQ_LAUNCH(64, true);
       else LG_DQ_LAUNCH(64, false);
-    } else {
+    } else if ((m.wb * m.b + LG_BF16_TQ) / LG_BF16_TK < 16) {
+      // few key tiles per query tile: the 8-wave kernel starts up and drains faster
       if (token) LG_DQ_LAUNCH(128, true);
       else LG_DQ_LAUNCH(128, false);
+    } else if (token) {
+      dq_wide_bf16_kernel<true><<<grid, 256, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv,
+                                                     sh.scale, m, nqt, total, per_xcd);
+    } else {
+      dq_wide_bf16_kernel<false><<<grid, 256, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv,
+                                                      sh.scale, m, nqt, total, per_xcd);
     }
 #undef LG_DQ_LAUNCH
     e = hipGetLastError();

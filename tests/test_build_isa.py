@@ -1,9 +1,9 @@
 """Generated-code checks for the kernels that name AGPR blocks directly.
 
-The 64-keys-per-wave dk/dv kernel keeps its 16 accumulators in fixed AGPR blocks that only its own
-inline matrix instructions touch.  That is only sound while the compiler itself puts nothing into
-AGPRs in that kernel and spills nothing; this test compiles the file to assembly (no GPU needed) and
-checks exactly that.
+The 64-keys-per-wave dk/dv kernel and the 64-rows-per-wave dq kernel keep their accumulators (and
+the dq kernel its Q / dO fragments) in fixed AGPR blocks that only their own inline statements
+touch.  That is only sound while the compiler itself puts nothing into AGPRs in those kernels and
+spills nothing; this test compiles the file to assembly (no GPU needed) and checks exactly that.
 """
 import os
 import re
@@ -34,47 +34,56 @@ def wide_kernels(tmp_path_factory):
     subprocess.run(cmd, check=True, capture_output=True, timeout=600)
     text = out.read_text()
     kernels = {}
-    for mt in re.finditer(r"^(_ZN\S*dkdv_wide_bf16_kernel\S*):.*?^\.Lfunc_end\d+:", text, re.S | re.M):
+    for mt in re.finditer(r"^(_ZN\S*(?:dkdv|dq)_wide_bf16_kernel\S*):.*?^\.Lfunc_end\d+:", text, re.S | re.M):
         kernels[mt.group(1)] = mt.group(0)
     meta = {}   # kernel name -> its entry in the code object metadata (one "- .agpr_count: ..." block each)
     for entry in re.split(r"\n  - (?=\.agpr_count:)", text):
-        mt = re.search(r"\.name:\s+(_ZN\S*dkdv_wide_bf16_kernel\S*)", entry)
+        mt = re.search(r"\.name:\s+(_ZN\S*(?:dkdv|dq)_wide_bf16_kernel\S*)", entry)
         if mt and entry.startswith(".agpr_count"):
             meta[mt.group(1)] = entry
     return kernels, meta, text
 
 
-def test_wide_dkdv_instances_present(wide_kernels):
+def test_wide_instances_present(wide_kernels):
     kernels, meta, _ = wide_kernels
-    assert len(kernels) == 2, sorted(kernels)          # TOKEN = true / false
+    assert len(kernels) == 4, sorted(kernels)          # two kernels, TOKEN = true / false
 
 
 def test_compiler_keeps_out_of_the_agprs(wide_kernels):
     kernels, _, _ = wide_kernels
     for name, body in kernels.items():
-        # nothing but the kernel's own statements may write an AGPR: they do so only as the
-        # destination of matrix instructions
-        assert "v_accvgpr_write" not in body, name
+        is_dq = "dq_wide" in name
+        nacc = 128 if is_dq else 256      # accumulator registers a0 .. a(nacc-1)
+        # the only AGPR writes besides matrix results: the dq kernel stores its 32 fragments once
+        writes = re.findall(r"v_accvgpr_write_b32\s+a(\d+),", body)
+        assert sorted(int(r) for r in writes) == (list(range(128, 256)) if is_dq else []), name
         assert "v_accvgpr_mov" not in body, name
-        # the copy-out reads each of the 256 accumulator registers exactly once
+        # the copy-out reads each accumulator register exactly once
         reads = re.findall(r"v_accvgpr_read_b32\s+v\d+,\s*a(\d+)", body)
-        assert sorted(int(r) for r in reads) == list(range(256)), name
-        # AGPRs appear otherwise only as matrix accumulators (destination == addend)
+        assert sorted(int(r) for r in reads) == list(range(nacc)), name
+        # otherwise AGPRs appear only in matrix instructions: as accumulator (destination == addend,
+        # inside the accumulator range) or, in the dq kernel, as the second operand (a fragment)
         for line in body.splitlines():
             line = line.split(";")[0]
-            if "a[" in line and "v_mfma" in line:
+            if "v_mfma" in line:
                 ops = [o.strip() for o in line.split(None, 1)[1].split(",")]
                 if ops[0].startswith("a["):
                     assert ops[3] in (ops[0], "0"), line
-            elif re.search(r"\ba\[\d+:\d+\]|\ba\d+\b", line) and "v_accvgpr_read" not in line:
-                raise AssertionError(f"{name}: AGPR used outside the accumulators: {line.strip()}")
+                    assert int(re.match(r"a\[(\d+):", ops[0]).group(1)) < nacc, line
+                else:
+                    assert not ops[3].startswith("a["), line
+                assert not ops[1].startswith("a["), line
+                if ops[2].startswith("a["):
+                    assert is_dq and int(re.match(r"a\[(\d+):", ops[2]).group(1)) >= 128, line
+            elif re.search(r"\ba\[\d+:\d+\]|\ba\d+\b", line) and "v_accvgpr_" not in line:
+                raise AssertionError(f"{name}: AGPR used outside the kernel's own statements: {line.strip()}")
 
 
-def test_no_spills_in_wide_dkdv(wide_kernels):
+def test_no_spills_in_wide_kernels(wide_kernels):
     kernels, meta, _ = wide_kernels
     for name, body in kernels.items():
         assert "scratch_" not in body, name
-    assert len(meta) == 2
+    assert len(meta) == 4
     for name, md in meta.items():
         assert re.search(r"\.private_segment_fixed_size:\s+0\b", md), name
         assert re.search(r"\.vgpr_spill_count:\s+0\b", md), name

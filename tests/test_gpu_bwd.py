@@ -95,6 +95,29 @@ def test_strided_columns_long_context(B, Hq, Hkv, N, D, sink, window, block, str
     check_bwd(B, Hq, Hkv, N, D, sink, window, block, stride, dtype=torch.bfloat16, seed=41)
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,sink,window,block,stride", [
+    # windows of 16 or more tiles at D = 128 select the kernels with 64 query rows / 64 keys per wave:
+    # token-granular with a ragged end (sink tile handled by the main instance); GQA with batch
+    # (column instance + partial sums folded into the main instance); block-granular; block-strided;
+    # no sink and a window longer than most rows
+    (1, 2, 2, 3001, 128, 64, 1024, 1, 0),
+    (2, 4, 2, 2500, 128, 3, 900, 1, 0),
+    (1, 2, 1, 3333, 128, 64, 1024, 64, 0),
+    (1, 2, 2, 4100, 128, 64, 1024, 64, 8),
+    (1, 1, 1, 2049, 128, 0, 2048, 1, 0),
+])
+def test_long_windows_wide_kernels(B, Hq, Hkv, N, D, sink, window, block, stride):
+    check_bwd(B, Hq, Hkv, N, D, sink, window, block, stride, dtype=torch.bfloat16, seed=77)
+
+
+def test_bwd_deterministic_long_window():
+    q, k, v, g = lg_synth.prefill_inputs(1, 2, 2, 2000, 128, 10, torch.bfloat16, with_dout=True)
+    a = run_fwd_bwd(q, k, v, g, 64, 1024)
+    b = run_fwd_bwd(q, k, v, g, 64, 1024)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
 def test_bwd_deterministic():
     # sink + window without GQA has no atomics anywhere: bit-identical from run to run (the partial dk/dv
     # sums of column keys in strided or GQA calls are added with float atomics, in no fixed order)
