@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # separate from timed runs, so these are constants here, not measured by this script.
 MEASURED_HBM_BYTES = {
     "fwd_bf16_kernel": (4.24e9, 1.090e9),
-    "dq_bf16_kernel": (5.57e9, 1.070e9),
-    "dkdv_bf16_kernel": (7.85e9, 2.260e9),
+    "dq_wide_bf16_kernel": (5.40e9, 1.070e9),
+    "dkdv_wide_bf16_kernel": (8.09e9, 2.150e9),
     "decode_kernel": (1.09e9, 0.000e9),
 }
 
@@ -121,8 +121,9 @@ def main():
     # recomputation of S and dP is not counted)
     kernels = [
         {"kernel": "fwd_bf16_kernel", "ms": fwd_ms, "flops": fl_fwd},
-        {"kernel": "dq_bf16_kernel", "ms": split[1], "flops": 6.0 * D * pairs},
-        {"kernel": "dkdv_bf16_kernel", "ms": split[2], "flops": 4.0 * D * pairs},
+        # (head dim 128 with a window of 16+ tiles: the library picks its 64-rows-per-wave kernels)
+        {"kernel": "dq_wide_bf16_kernel", "ms": split[1], "flops": 6.0 * D * pairs},
+        {"kernel": "dkdv_wide_bf16_kernel", "ms": split[2], "flops": 4.0 * D * pairs},
     ]
     for kk in kernels:
         kk["tflops"] = kk["flops"] / (kk["ms"] * 1e-3) / 1e12
