@@ -65,18 +65,25 @@ struct LgDma {
   // from there on (rows past the end are replaced by the last valid row); lds: LDS byte
   // address of the tile (wave-uniform).
   __device__ __forceinline__ void issue(const uint16_t* src, int rows_left, uint32_t lds) const {
+    // two copies of the loop behind one wave-uniform branch: whole tiles (nearly all) spend no
+    // vector instructions on addresses
+    if (rows_left >= T::ROWS) {
 #pragma unroll
-    for (int x = 0; x < CH; ++x) {
-      uint32_t off = voff[x];
-      if (rows_left < T::ROWS) {  // ragged tile: rows past the end repeat the last valid row
-        const int row = (int)(off / T::ROW_BYTES);
+      for (int x = 0; x < CH; ++x) load(src, voff[x], lds, x);
+    } else {  // ragged tile: rows past the end repeat the last valid row
+#pragma unroll
+      for (int x = 0; x < CH; ++x) {
+        const int row = (int)(voff[x] / T::ROW_BYTES);
         const int r = min(row, rows_left - 1);
-        off = off - row * T::ROW_BYTES + r * T::ROW_BYTES;
+        load(src, voff[x] - row * T::ROW_BYTES + r * T::ROW_BYTES, lds, x);
       }
-      const uint32_t m0 = lds + wave_off + x * NT * 16;  // all scalar
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(m0)), "v"(off), "s"(src)
-                   : "memory");
     }
+  }
+  __device__ __forceinline__ void load(const uint16_t* src, uint32_t off, uint32_t lds, int x) const {
+    const uint32_t m0 = lds + wave_off + x * NT * 16;  // all scalar
+    // (an LDS-bound load reads M0 one issue slot after a scalar write at the earliest)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(m0)), "v"(off), "s"(src)
+                 : "memory");
   }
 };
 
@@ -84,7 +91,7 @@ struct LgDma {
 // (src is this lane's own address) and the wave's 256 bytes land contiguously at `lds`.
 __device__ __forceinline__ void lg_dma_f32x64(const float* lane_src, uint32_t lds) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(m0), "v"(lane_src) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(m0), "v"(lane_src) : "memory");
 }
 
 // Per-lane read offsets into a swizzled tile (lane = 32g + n).  Only two lane-dependent
