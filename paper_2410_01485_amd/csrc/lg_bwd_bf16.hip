@@ -1053,7 +1053,6 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
   static_assert(TQ == 256 && TK == 64, "4 waves x 64 query rows, 64-key tiles");
   constexpr int DC = D / 16, DB = D / 32;
   constexpr int STAGE = 2 * T::BYTES;  // K tile + V tile
-  constexpr int LPT = 2 * Dma::CH;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[STAGES * STAGE];
 
   const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -1110,29 +1109,31 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
     if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
     return lg_qsched_next(m, qs, prev);
   };
+  // Tiles are handled in pairs: one barrier per two tiles (with one wave per SIMD nothing hides the
+  // wait for the slowest wave, so fewer barriers matter more than a deeper ring).  Pair p lives in
+  // stages 2 (p % 2), + 1; at its start the loads of pair p + 1 go into the other two stages.
   int t = next_tile(-1);
   int t_issue = t;
-  int ahead = 0;
-  for (; ahead < STAGES - 1 && t_issue >= 0; ++ahead) {
-    issue(t_issue, ahead);
+  for (int x = 0; x < 2 && t_issue >= 0; ++x) {
+    issue(t_issue, x);
     t_issue = next_tile(t_issue);
   }
   int stage = 0;
   while (t >= 0) {
-    if (ahead >= 3) LG_WAIT_VMCNT(2 * LPT);
-    else if (ahead == 2) LG_WAIT_VMCNT(LPT);
-    else LG_WAIT_VMCNT(0);
-    __syncthreads();  // tile t landed for everyone; everyone is done with tile t-1
-    if (t_issue >= 0) {
-      issue(t_issue, (stage + STAGES - 1) % STAGES);
-      t_issue = next_tile(t_issue);
-      ++ahead;
+    if ((stage & 1) == 0) {
+      LG_WAIT_VMCNT(0);
+      __syncthreads();  // this pair landed for everyone; everyone is done with the previous pair
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+        if (t_issue >= 0) {
+          issue(t_issue, (stage + 2 + x) % STAGES);
+          t_issue = next_tile(t_issue);
+        }
     }
     const int k0 = t * TK;
     int kind = LG_TILE_FULL;
     if (!lg_qsched_full(m, qs, t)) kind = lg_tile_kind(m, qw0, qw1, k0, k0 + TK - 1);
     const int sk = stage * STAGE, sv = sk + T::BYTES;
-    --ahead;
     t = next_tile(t);
     stage = (stage + 1) % STAGES;
     if (kind == LG_TILE_DEAD) continue;
