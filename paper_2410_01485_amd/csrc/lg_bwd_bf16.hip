@@ -19,10 +19,15 @@
 //  of a wave stays in registers, the V rows of the workgroup stay in LDS).  Per live query
 //  tile of 64 rows, for every query head of the kv group:
 //     S  = Q K^T,  dP = dO V^T          (queries x keys; A = Q / dO rows from LDS)
-//     P, dS as above                    (one key per lane; lse / Delta read per row)
+//     P, dS as above                    (one key per lane; S and dP start from the per-row
+//                                        values -lse / scale and -Delta as their addend)
 //     dV^T += dO^T P,  dK^T += Q^T dS   (dims x keys; A = dO / Q through transposing reads,
 //                                        B = P / dS straight from the accumulators)
 // 7 tile products instead of the minimal 5: S and dP are computed in both kernels.
+//
+// For head dim 128 and windows of 16 or more tiles both kernels have a second form with 64 rows
+// (keys) per wave, one wave per SIMD and the accumulators in AGPRs (further down): every operand
+// read from LDS then feeds two matrix instructions.
 #include "../../include/longgen_attn.h"
 #include "lg_kernels.h"
 #include "lg_mfma.h"
@@ -957,7 +962,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 
 // ------------------------------------------------- dq: 64 query rows per wave (D = 128)
 // Same idea as the wide dk/dv kernel: four waves of 64 query rows, so that every K / V operand
-// read from LDS feeds two matrix instructions.  The AGPR half of the register file holds the dq
+// read from LDS feeds two matrix instructions; same tile walk as the 8-wave kernel, the 4-stage ring
+// used as two pairs of tiles with one barrier per pair.  The AGPR half of the register file holds the dq
 // accumulators (blocks 0..7 = a[0:127]: row block rb, dim block db -> block 4 rb + db) and the
 // wave's Q and dO fragments (a[128:255], four registers per 32 rows x 16 dims), which the matrix
 // instructions read as their second operand straight from there.
