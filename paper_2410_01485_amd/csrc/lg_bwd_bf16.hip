@@ -984,6 +984,9 @@ struct LgFrag;
     static __device__ __forceinline__ void mul(f32x16_t& c, bf16x8_t a) {                                      \
       asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #LO ":" #HI "], 0" : "=&v"(c) : "v"(a));               \
     }                                                                                                          \
+    static __device__ __forceinline__ void mad(f32x16_t& c, bf16x8_t a, const f32x16_t& init) {                \
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[" #LO ":" #HI "], %2" : "=&v"(c) : "v"(a), "v"(init));   \
+    }                                                                                                          \
   };
 LG_FRAG(0, 128, 131, 128, 129, 130, 131)
 LG_FRAG(1, 132, 135, 132, 133, 134, 135)
@@ -1023,6 +1026,12 @@ LG_FRAG(31, 252, 255, 252, 253, 254, 255)
 // i is a compile-time constant at every call: the switch folds away
 __device__ __forceinline__ void lg_frag_set(int i, uint4 v) {
 #define LG_OP(I) LgFrag<I>::set(v)
+  LG_FRAG_CASES(LG_OP)
+#undef LG_OP
+}
+// c = init + a * fragment i
+__device__ __forceinline__ void lg_frag_mfma_init(int i, f32x16_t& c, bf16x8_t a, const f32x16_t& init) {
+#define LG_OP(I) LgFrag<I>::mad(c, a, init)
   LG_FRAG_CASES(LG_OP)
 #undef LG_OP
 }
@@ -1081,7 +1090,8 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
   const int i0 = q0 + wave * 64 + n;  // this lane's row of row block 0 (block 1: + 32)
 
   // fragments: Q of (rb, dc) -> fragment 8 rb + dc, dO -> 16 + 8 rb + dc
-  float lse2[2], di[2];
+  float lse2[2];
+  f32x16_t ndl[2];  // -Delta of the lane's row in all 16 registers: the addend dP^T starts from
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int iq = min(i0 + 32 * rb, N - 1);
@@ -1091,10 +1101,12 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
       lg_frag_set(16 + 8 * rb + dc, *reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8));
     }
     lse2[rb] = lse[(size_t)(b * Hq + hq) * N + iq] * LOG2E;
-    di[rb] = ndelta[(size_t)(b * Hq + hq) * N + iq];  // -Delta
+    const float nd = ndelta[(size_t)(b * Hq + hq) * N + iq];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ndl[rb][r] = nd;
   }
   const float sl2 = scale * LOG2E;
-  asm volatile("" : "+v"(lse2[0]), "+v"(lse2[1]), "+v"(di[0]), "+v"(di[1]));
+  asm volatile("" : "+v"(lse2[0]), "+v"(lse2[1]), "+v"(ndl[0]), "+v"(ndl[1]));
   const bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
 #pragma unroll
   for (int x = 0; x < 8; ++x) lg_acc_zero(x, zero8);
@@ -1199,8 +1211,7 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
     };
     auto ds_piece = [&](int kb, int x) {
       const int rb = (x >> 2) & 1, h = x >> 3, r = 8 * h + 2 * (x & 3);
-      wD[kb][rb][h][x & 3] = lg_pack_bf16(sc[kb][rb][r] * (dp[kb][rb][r] + di[rb]),
-                                          sc[kb][rb][r + 1] * (dp[kb][rb][r + 1] + di[rb]));
+      wD[kb][rb][h][x & 3] = lg_pack_bf16(sc[kb][rb][r] * dp[kb][rb][r], sc[kb][rb][r + 1] * dp[kb][rb][r + 1]);
     };
     auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
 
@@ -1213,7 +1224,8 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
         constexpr int u = mi >> 1, rb = mi & 1, sl = u % NSL, c = u & 7, ph = u >> 3;
         if (rb == 0 && u + DIST < 48) reads(u + DIST);
         if (ph == 0 || ph == 2) lg_frag_mfma(8 * rb + c, c == 0, sc[ph >> 1][rb], ra[sl]);
-        else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, c == 0, dp[ph >> 1][rb], ra[sl]);
+        else if ((ph == 1 || ph == 3) && c == 0) lg_frag_mfma_init(16 + 8 * rb, dp[ph >> 1][rb], ra[sl], ndl[rb]);
+        else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, false, dp[ph >> 1][rb], ra[sl]);
         else lg_acc_fma(4 * rb + (c & 3), ra[sl], bop(wD[ph - 4][rb][c >> 2]));
         // S / dP are final six matrix instructions after their last one
         if (mi == 21) lg_tie(sc[0][0], sc[0][1]);
