@@ -5,7 +5,7 @@
 
 One step = the training pass of one sparse layer on the Llama-2-7B-shaped 128K workload
 (B1, 32 heads, D128, N131072, bf16, sink 64 + window 4096): forward (out, lse) followed by
-backward (Delta pre-pass, dq kernel, dk/dv kernel), inputs resident in HBM.  The headline
+backward (dq kernel, which also forms Delta, and dk/dv kernel), inputs resident in HBM.  The headline
 value is effective TFLOP/s: algorithmic flops of the live (query, key) pairs (4*D forward,
 10*D backward per pair per head) divided by the measured step time.  The same run also times
 decode over the 64+4096-slot ring cache (B16, 32 heads) and the fp64 CPU oracle on a bounded

@@ -1,7 +1,7 @@
 // lg_bwd_bf16.hip — bf16 backward on the gfx950 matrix cores (paper Section 3.2: the
 // backward step skips masked key blocks just like the forward; Table 1 counts both).
 //
-// Two kernels after the Delta pre-pass.  Sink + window without GQA uses no atomics and is
+// Two kernels (the first one also forms Delta).  Sink + window without GQA uses no atomics and is
 // bit-reproducible; strided patterns and GQA add float32 partial dk/dv sums of the column keys
 // with atomics (see the dk/dv section).  Tiles
 // travel global -> LDS directly (row-major, swizzled; lg_swz.h) and are read both with the
@@ -44,12 +44,27 @@ constexpr float LOG2E = 1.44269504088896340736f;
 // arithmetic from the per-tile scheduling, and partial tiles are masked with two compares per
 // element instead of a per-element evaluation of the general predicate.
 
+// sum over 8 bf16 pairs of x * y, added to s
+__device__ __forceinline__ float lg_dot8(uint4 x, uint4 y, float s) {
+  const unsigned xw[4] = {x.x, x.y, x.z, x.w}, yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    s = fmaf(__uint_as_float(xw[t] << 16), __uint_as_float(yw[t] << 16), s);
+    s = fmaf(__uint_as_float(xw[t] & 0xffff0000u), __uint_as_float(yw[t] & 0xffff0000u), s);
+  }
+  return s;
+}
+
+// Both dq kernels also form Delta_i = <dout_i, out_i> of their rows (a lane and its partner in
+// the other half of the wave hold the whole row of dout anyway) and leave -Delta and -lse / scale
+// in the workspace for the dk/dv kernels, which run after them on the same stream.
 // ------------------------------------------------------------------------- dq
 template <int D, bool TOKEN>
 __global__ __launch_bounds__(512) void dq_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ ndelta,
-    uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m_in, int nqt, int total, int per_xcd) {
+    const uint16_t* __restrict__ out, const uint16_t* __restrict__ dout, const float* __restrict__ lse,
+    float* __restrict__ ndelta, float* __restrict__ nlse, uint16_t* __restrict__ dq, int Hq, int Hkv, float scale,
+    LgMask m_in, int nqt, int total, int per_xcd) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -92,14 +107,22 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
   const int qw0 = min(q0 + wave_s * 32, N - 1), qw1 = min(q0 + wave_s * 32 + 31, N - 1);  // this wave's rows
 
   bf16x8_t qf[DC], gf[DC];
+  float di = 0.f;
 #pragma unroll
   for (int dc = 0; dc < DC; ++dc) {
+    const uint4 gw = *reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8);
     qf[dc] = lg_as_bf16x8(*reinterpret_cast<const uint4*>(q + qbase + (size_t)iq * D + dc * 16 + g * 8));
-    gf[dc] = lg_as_bf16x8(*reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8));
+    gf[dc] = lg_as_bf16x8(gw);
+    di = lg_dot8(gw, *reinterpret_cast<const uint4*>(out + qbase + (size_t)iq * D + dc * 16 + g * 8), di);
   }
+  di += lg_other_half(di);  // Delta of row i
   const float sl2 = scale * LOG2E;
-  float lse2 = lse[(size_t)(b * Hq + hq) * N + iq] * LOG2E;
-  float di = -ndelta[(size_t)(b * Hq + hq) * N + iq];  // the pre-pass stores -Delta
+  const float lse_i = lse[(size_t)(b * Hq + hq) * N + iq];
+  float lse2 = lse_i * LOG2E;
+  if (g == 0 && i < N) {
+    ndelta[(size_t)(b * Hq + hq) * N + i] = -di;
+    nlse[(size_t)(b * Hq + hq) * N + i] = -lse_i / scale;
+  }
   // Touch everything loaded so far, so that the compiler's waits for these loads sit here and
   // not inside the tile loop (where they would drain the direct loads kept in flight).
 #pragma unroll
@@ -635,6 +658,9 @@ __device__ __forceinline__ void lg_mfma_v(f32x16_t& c, bf16x8_t a, bf16x8_t b) {
 __device__ __forceinline__ void lg_mfma_vi(f32x16_t& c, bf16x8_t a, bf16x8_t b, const f32x16_t& init) {  // c = a b + init
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(c) : "v"(a), "v"(b), "v"(init));
 }
+// Operands that vector instructions produce (P / dS rounded to bf16, the zero operand) must be
+// complete a few issue slots before the matrix instruction that reads them: the pieces that produce
+// P / dS end at least one matrix instruction earlier, the zero operand is followed by idle slots.
 // Program-order anchor without an instruction: everything that reads x or y is placed after this
 // point, everything that wrote them before it.  A vector instruction may read a matrix result
 // only ~20 issue slots after the matrix instruction was issued; the anchors are set where at
@@ -725,7 +751,10 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     for (int dc = 0; dc < DC; ++dc) asm volatile("" ::"v"(kf[kb][dc]));
 
   // accumulators: dk of key block kb, dim block db = block kb * 4 + db; dv = block 8 + kb * 4 + db
-  const bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+  bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+  // A matrix instruction must not read a register that a vector instruction wrote just before it
+  // (the compiler spaces its own; an inline one that followed the write directly read stale lanes).
+  asm volatile("s_nop 15" : "+v"(zero8));
 #pragma unroll
   for (int i = 0; i < 16; ++i) lg_acc_zero(i, zero8);
 
@@ -1049,8 +1078,9 @@ __device__ __forceinline__ void lg_frag_mfma(int i, bool first, f32x16_t& c, bf1
 template <bool TOKEN>
 __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ ndelta,
-    uint16_t* __restrict__ dq, int Hq, int Hkv, float scale, LgMask m_in, int nqt, int total, int per_xcd) {
+    const uint16_t* __restrict__ out, const uint16_t* __restrict__ dout, const float* __restrict__ lse,
+    float* __restrict__ ndelta, float* __restrict__ nlse, uint16_t* __restrict__ dq, int Hq, int Hkv, float scale,
+    LgMask m_in, int nqt, int total, int per_xcd) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -1090,24 +1120,40 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
   const int i0 = q0 + wave * 64 + n;  // this lane's row of row block 0 (block 1: + 32)
 
   // fragments: Q of (rb, dc) -> fragment 8 rb + dc, dO -> 16 + 8 rb + dc
-  float lse2[2];
+  float lse2[2], lse_i[2];
   f32x16_t ndl[2];  // -Delta of the lane's row in all 16 registers: the addend dP^T starts from
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int iq = min(i0 + 32 * rb, N - 1);
+    float di = 0.f;
 #pragma unroll
     for (int dc = 0; dc < DC; ++dc) {
+      const uint4 gw = *reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8);
       lg_frag_set(8 * rb + dc, *reinterpret_cast<const uint4*>(q + qbase + (size_t)iq * D + dc * 16 + g * 8));
-      lg_frag_set(16 + 8 * rb + dc, *reinterpret_cast<const uint4*>(dout + qbase + (size_t)iq * D + dc * 16 + g * 8));
+      lg_frag_set(16 + 8 * rb + dc, gw);
+      di = lg_dot8(gw, *reinterpret_cast<const uint4*>(out + qbase + (size_t)iq * D + dc * 16 + g * 8), di);
     }
-    lse2[rb] = lse[(size_t)(b * Hq + hq) * N + iq] * LOG2E;
-    const float nd = ndelta[(size_t)(b * Hq + hq) * N + iq];
+    di += lg_other_half(di);  // Delta of the row
+    lse_i[rb] = lse[(size_t)(b * Hq + hq) * N + iq];
+    lse2[rb] = lse_i[rb] * LOG2E;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) ndl[rb][r] = nd;
+    for (int r = 0; r < 16; ++r) ndl[rb][r] = -di;
   }
   const float sl2 = scale * LOG2E;
   asm volatile("" : "+v"(lse2[0]), "+v"(lse2[1]), "+v"(ndl[0]), "+v"(ndl[1]));
-  const bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+  {  // The rows' -Delta and -lse / scale for the dk/dv kernels.  Every lane stores, without a branch:
+     // the two lanes of a row store the same values, and lanes past the end hold (and store) those
+     // of row N - 1, whose data they loaded.
+    const float inv_scale = 1.f / scale;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const size_t row = (size_t)(b * Hq + hq) * N + min(i0 + 32 * rb, N - 1);
+      ndelta[row] = ndl[rb][0];
+      nlse[row] = -lse_i[rb] * inv_scale;
+    }
+  }
+  bf16x8_t zero8 = lg_as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+  asm volatile("s_nop 15" : "+v"(zero8));  // as in the dk/dv kernel: written well before it is read
 #pragma unroll
   for (int x = 0; x < 8; ++x) lg_acc_zero(x, zero8);
 
@@ -1223,10 +1269,11 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
         constexpr int mi = decltype(M)::value;
         constexpr int u = mi >> 1, rb = mi & 1, sl = u % NSL, c = u & 7, ph = u >> 3;
         if (rb == 0 && u + DIST < 48) reads(u + DIST);
-        if (ph == 0 || ph == 2) lg_frag_mfma(8 * rb + c, c == 0, sc[ph >> 1][rb], ra[sl]);
-        else if ((ph == 1 || ph == 3) && c == 0) lg_frag_mfma_init(16 + 8 * rb, dp[ph >> 1][rb], ra[sl], ndl[rb]);
-        else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, false, dp[ph >> 1][rb], ra[sl]);
-        else lg_acc_fma(4 * rb + (c & 3), ra[sl], bop(wD[ph - 4][rb][c >> 2]));
+        constexpr int kb = ph < 4 ? ph >> 1 : ph - 4;  // key block of the unit
+        if (ph == 0 || ph == 2) lg_frag_mfma(8 * rb + c, c == 0, sc[kb][rb], ra[sl]);
+        else if ((ph == 1 || ph == 3) && c == 0) lg_frag_mfma_init(16 + 8 * rb, dp[kb][rb], ra[sl], ndl[rb]);
+        else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, false, dp[kb][rb], ra[sl]);
+        else lg_acc_fma(4 * rb + (c & 3), ra[sl], bop(wD[kb][rb][c >> 2]));
         // S / dP are final six matrix instructions after their last one
         if (mi == 21) lg_tie(sc[0][0], sc[0][1]);
         if (mi == 37) lg_tie(dp[0][0], dp[0][1]);
@@ -1319,11 +1366,11 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
   const size_t row_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
   float* ndelta = (float*)ws;
   float* nlse = (float*)((char*)ws + row_bytes);
+  // (no separate pre-pass on this path: the dq kernel forms Delta and writes both arrays)
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = lg_launch_delta(dout, out, ndelta, lse, nlse, -1.f, -1.f / sh.scale,
-                                 (long long)sh.B * sh.Hq * sh.N, sh.D, LG_BF16, s);
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
   if (ev) (void)hipEventRecord(ev[1], s);
+  const uint16_t* uo = (const uint16_t*)out;
   const uint16_t* uq = (const uint16_t*)q;
   const uint16_t* uk = (const uint16_t*)k;
   const uint16_t* uv = (const uint16_t*)v;
@@ -1336,8 +1383,8 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const int total = (int)tl, per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8);
 #define LG_DQ_LAUNCH(DD, TT)                                                                        \
-  dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv, \
-                                              sh.scale, m, nqt, total, per_xcd)
+  dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq, \
+                                              sh.Hkv, sh.scale, m, nqt, total, per_xcd)
     if (sh.D == 64) {
       if (token) LG_DQ_LAUNCH(64, true);
       else LG_DQ_LAUNCH(64, false);
@@ -1346,11 +1393,11 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
       if (token) LG_DQ_LAUNCH(128, true);
       else LG_DQ_LAUNCH(128, false);
     } else if (token) {
-      dq_wide_bf16_kernel<true><<<grid, 256, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv,
-                                                     sh.scale, m, nqt, total, per_xcd);
+      dq_wide_bf16_kernel<true><<<grid, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
+                                                     sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     } else {
-      dq_wide_bf16_kernel<false><<<grid, 256, 0, s>>>(uq, uk, uv, ug, lse, ndelta, (uint16_t*)dq, sh.Hq, sh.Hkv,
-                                                      sh.scale, m, nqt, total, per_xcd);
+      dq_wide_bf16_kernel<false><<<grid, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
+                                                      sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     }
 #undef LG_DQ_LAUNCH
     e = hipGetLastError();

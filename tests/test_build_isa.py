@@ -88,3 +88,47 @@ def test_no_spills_in_wide_kernels(wide_kernels):
         assert re.search(r"\.private_segment_fixed_size:\s+0\b", md), name
         assert re.search(r"\.vgpr_spill_count:\s+0\b", md), name
         assert re.search(r"\.agpr_count:\s+256\b", md), name
+
+
+def _regs(op):
+    """VGPR numbers named by one operand (v12, v[4:7]); AGPRs and everything else: none."""
+    mt = re.match(r"v\[(\d+):(\d+)\]$", op)
+    if mt:
+        return set(range(int(mt.group(1)), int(mt.group(2)) + 1))
+    mt = re.match(r"v(\d+)$", op)
+    return {int(mt.group(1))} if mt else set()
+
+
+def test_matrix_operands_are_not_written_just_before_use(wide_kernels):
+    """An inline matrix instruction that read a register right after a vector instruction wrote it
+    got stale lanes (the compiler spaces its own instructions, not inline ones).  The kernels keep
+    every such write at least one matrix instruction (or a long s_nop) ahead; check the generated
+    code: between a matrix instruction and the previous one (or the previous s_nop of 8+ slots),
+    no vector instruction may write one of its VGPR operands."""
+    kernels, _, _ = wide_kernels
+    for name, body in kernels.items():
+        written = {}          # VGPR -> text of the vector instruction that wrote it since the last fence
+        for raw in body.splitlines():
+            line = raw.split(";")[0].strip()
+            if not line or line.startswith(".") or line.endswith(":"):
+                if line.endswith(":"):
+                    written = dict(written)   # labels: keep (conservative: straight-line and joins alike)
+                continue
+            op = line.split()[0]
+            ops = [o.strip() for o in line.split(None, 1)[1].split(",")] if " " in line else []
+            if op.startswith("v_mfma"):
+                for src in ops[1:4]:
+                    hit = _regs(src) & set(written)
+                    assert not hit, f"{name}: {line}  reads v{min(hit)} written by: {written[min(hit)]}"
+                written = {}
+            elif op == "s_nop" and ops and int(ops[0]) >= 7:
+                written = {}
+            elif op.startswith(("ds_read", "global_load", "buffer_load", "scratch_load")) and "lds" not in op:
+                for r in _regs(ops[0]) if ops else ():   # reloaded from memory: waited for by counter
+                    written.pop(r, None)
+            elif op.startswith("v_") and not op.startswith("v_accvgpr_write") and not op.startswith("v_cmp"):
+                for r in _regs(ops[0]) if ops else ():
+                    written[r] = line
+                if op.startswith("v_permlane32_swap") and len(ops) > 1:
+                    for r in _regs(ops[1]):
+                        written[r] = line
