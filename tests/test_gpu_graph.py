@@ -11,8 +11,12 @@ from gpu_util import DEV
 pytestmark = pytest.mark.gpu
 
 
-def test_graph_replay_matches_eager():
-    B, Hq, Hkv, N, D, sink, window, block, stride = 1, 4, 2, 5000, 128, 64, 128, 64, 4   # has column parts
+@pytest.mark.parametrize("window,stride", [
+    (128, 4),     # short window: the 8-wave backward kernels; column parts
+    (1024, 8),    # long window at head dim 128: the 64-rows-per-wave backward kernels; column parts
+])
+def test_graph_replay_matches_eager(window, stride):
+    B, Hq, Hkv, N, D, sink, block = 1, 4, 2, 5000, 128, 64, 64
     dt = torch.bfloat16
     q, k, v, g = (x.to(DEV) for x in lg_synth.prefill_inputs(B, Hq, Hkv, N, D, 71, dt, with_dout=True))
     out = torch.empty_like(q)
