@@ -31,26 +31,6 @@ struct LgAcc;
       asm volatile("v_mfma_f32_32x32x16_bf16 a[" #LO ":" #HI "], %0, %0, 0" ::"v"(z) \
                    : LG_ACC_CLOBBER(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15)); \
     } \
-    static __device__ __forceinline__ void scale(float alpha) { \
-      float t; \
-      asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R0 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R1 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R1 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R2 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R2 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R3 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R3 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R4 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R4 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R5 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R5 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R6 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R6 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R7 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R7 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R8 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R8 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R9 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R9 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R10 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R10 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R11 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R11 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R12 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R12 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R13 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R13 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R14 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R14 ", %0\n\t" \
-                   "v_accvgpr_read_b32 %0, a" #R15 "\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a" #R15 ", %0\n\t" \
-                   : "=&v"(t) : "v"(alpha) : LG_ACC_CLOBBER(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15)); \
-    } \
     static __device__ __forceinline__ void get(float* x) { \
       asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\t" "v_accvgpr_read_b32 %1, a" #R1 "\n\t" "v_accvgpr_read_b32 %2, a" #R2 "\n\t" "v_accvgpr_read_b32 %3, a" #R3 "\n\t" "v_accvgpr_read_b32 %4, a" #R4 "\n\t" "v_accvgpr_read_b32 %5, a" #R5 "\n\t" "v_accvgpr_read_b32 %6, a" #R6 "\n\t" "v_accvgpr_read_b32 %7, a" #R7 "\n\t" "v_accvgpr_read_b32 %8, a" #R8 "\n\t" "v_accvgpr_read_b32 %9, a" #R9 "\n\t" "v_accvgpr_read_b32 %10, a" #R10 "\n\t" "v_accvgpr_read_b32 %11, a" #R11 "\n\t" "v_accvgpr_read_b32 %12, a" #R12 "\n\t" "v_accvgpr_read_b32 %13, a" #R13 "\n\t" "v_accvgpr_read_b32 %14, a" #R14 "\n\t" "v_accvgpr_read_b32 %15, a" #R15 "\n\t" \
                    : "=v"(x[0]), "=v"(x[1]), "=v"(x[2]), "=v"(x[3]), "=v"(x[4]), "=v"(x[5]), "=v"(x[6]), "=v"(x[7]), "=v"(x[8]), "=v"(x[9]), "=v"(x[10]), "=v"(x[11]), "=v"(x[12]), "=v"(x[13]), "=v"(x[14]), "=v"(x[15])); \
@@ -88,13 +68,6 @@ __device__ __forceinline__ void lg_acc_fma(int i, bf16x8_t a, bf16x8_t b) {
 }
 __device__ __forceinline__ void lg_acc_zero(int i, bf16x8_t z) {
 #define LG_OP(I) LgAcc<I>::zero(z)
-  LG_ACC_CASES(LG_OP)
-#undef LG_OP
-}
-// block i *= alpha (vector instructions on AGPR contents: the caller makes sure no matrix
-// instruction that writes the block is still in flight, and none reads it right afterwards)
-__device__ __forceinline__ void lg_acc_scale(int i, float alpha) {
-#define LG_OP(I) LgAcc<I>::scale(alpha)
   LG_ACC_CASES(LG_OP)
 #undef LG_OP
 }
