@@ -258,20 +258,57 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
 constexpr int LG_COL_CHUNK = 64;  // query tiles (64 rows each) per column workgroup
 
 // col_of_group[c] = index of 64-key group c among the column groups, or -1; col_list = inverse.
-__global__ void dkdv_column_table_kernel(int* __restrict__ col_of_group, int* __restrict__ col_list,
-                                         LgMask m, int ngroups) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  int n = 0;
-  for (int c = 0; c < ngroups; ++c) {
-    const bool is = lg_is_column_group(m, c, LG_BF16_BTK, LG_BF16_BTQ);
-    col_of_group[c] = is ? n : -1;
-    if (is) col_list[n++] = c;
+// One workgroup of 1024 threads, 1024 groups per round: ranks from a ballot per wave plus the
+// counts of the waves before it.
+__global__ __launch_bounds__(1024) void dkdv_column_table_kernel(int* __restrict__ col_of_group,
+                                                                 int* __restrict__ col_list, LgMask m, int ngroups) {
+  __shared__ int wcount[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int base = 0;
+  for (int c0 = 0; c0 < ngroups; c0 += 1024) {
+    const int c = c0 + tid;
+    const bool is = c < ngroups && lg_is_column_group(m, c, LG_BF16_BTK, LG_BF16_BTQ);
+    const unsigned long long bal = __ballot(is);
+    if (lane == 0) wcount[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base, all = 0;
+    for (int w = 0; w < 16; ++w) {
+      if (w < wave) off += wcount[w];
+      all += wcount[w];
+    }
+    const int rank = off + __popcll(bal & ((1ull << lane) - 1ull));
+    if (c < ngroups) col_of_group[c] = is ? rank : -1;
+    if (is) col_list[rank] = c;
+    base += all;
+    __syncthreads();
   }
 }
 
 __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4) {
   for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < n4; x += (size_t)gridDim.x * blockDim.x)
     p[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// Adds a 32 x 32 accumulator block (lane (n, g), register r <-> row n, column 8 (r / 4) + 4 g + r % 4)
+// to dst[row * ld + column], rows below nrows only, with float32 atomics.  The block is turned
+// through 4 KB of LDS that belong to the calling wave (16-byte chunks XOR-swizzled by row), so that
+// one atomic instruction adds two whole rows of 32 consecutive floats -- two cache lines --
+// instead of two floats in each of 32 lines, which is what bounds the column instances otherwise.
+template <typename Acc>
+__device__ __forceinline__ void lg_atomic_add_block(float* tr, const Acc& acc, float* dst, int ld, int nrows,
+                                                    int n, int g) {
+#pragma unroll
+  for (int r4 = 0; r4 < 4; ++r4)
+    *reinterpret_cast<float4*>(tr + n * 32 + 4 * ((2 * r4 + g) ^ (n & 7))) =
+        make_float4(acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // (one wave: its LDS accesses complete in order)
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const int row = 2 * it + g;
+    const float x = tr[row * 32 + 4 * ((n >> 2) ^ (row & 7)) + (n & 3)];
+    if (row < nrows) unsafeAtomicAdd(dst + (size_t)row * ld + n, x);  // hardware float add in L2
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
 // ncol: column groups handled by the COLUMN instance (0: none are split off)
@@ -533,16 +570,15 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 
   // partial sums of the column parts: [b x kv head][column group][64 keys][D] float32, dk unscaled
   if (COLUMN) {
-    if (active && j < N) {
-      const size_t prow = (((size_t)bh * ncol + col_gi) * 64 + (wave_s & 1) * 32 + n) * D;
+    // the wave's own V rows (only this wave ever read them) serve as the turning space
+    static_assert(HALF >= 4096, "a 32 x 32 float block fits the wave's V rows");
+    float* tr = reinterpret_cast<float*>(smem + voff);
+    const int nrows = active ? min(max(N - kw0, 0), 32) : 0;
+    const size_t prow = (((size_t)bh * ncol + col_gi) * 64 + (wave_s & 1) * 32) * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int d = db * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          unsafeAtomicAdd(part_dk + prow + d, ak[db][r]);  // hardware float add in L2
-          unsafeAtomicAdd(part_dv + prow + d, av[db][r]);
-        }
+    for (int db = 0; db < DB; ++db) {
+      lg_atomic_add_block(tr, ak[db], part_dk + prow + db * 32, D, nrows, n, g);
+      lg_atomic_add_block(tr, av[db], part_dv + prow + db * 32, D, nrows, n, g);
     }
     return;
   }
@@ -585,13 +621,16 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 // matrix instructions of a function, so the instructions are written out with their register
 // classes here; that leaves their dependency waits, which the compiler otherwise provides, to
 // this code (see the notes at lg_tie and in the step).
-template <bool TOKEN>
+// COLUMN: the instance for the split-off column parts, as in the 8-wave kernel: a virtual tile of
+// four 64-key column groups, one group per wave, one chunk of the query range per workgroup,
+// float32 atomics into the partial sums.
+template <bool TOKEN, bool COLUMN>
 __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
-    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group,
-    const float* __restrict__ part_dk, const float* __restrict__ part_dv, int ncol) {
+    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
+    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -620,8 +659,19 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   const int n = lane & 31, g = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   // work item: as in the kernel above
-  int bh, kt;
-  if (ncol > 0) {
+  int bh, kt = 0, vt = 0, chunk = 0, gq = 0;
+  if (COLUMN) {
+    const int nvt = (ncol + 3) / 4;
+    // (the results of these divisions are pinned to scalar registers: the global->LDS copies take
+    // their base addresses, which derive from them, as scalar operands)
+    int x = blockIdx.x;
+    chunk = __builtin_amdgcn_readfirstlane(x % nchunk);
+    x /= nchunk;
+    vt = __builtin_amdgcn_readfirstlane(x % nvt);
+    x /= nvt;
+    gq = __builtin_amdgcn_readfirstlane(x % G);
+    bh = __builtin_amdgcn_readfirstlane(x / G);
+  } else if (ncol > 0) {
     const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (L >= total) return;
     bh = L / nkt;
@@ -642,7 +692,20 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   const int b = bh / Hkv, hk = bh % Hkv;
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
   const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
-  const int kw0 = k0 + wave_s * 64;  // this wave's 64 keys: lane n holds keys kw0 + n and kw0 + 32 + n
+  // this wave's 64 keys: a quarter of the key tile, or one column group of the virtual tile;
+  // lane n holds keys kw0 + n and kw0 + 32 + n
+  int kw0 = k0 + wave_s * 64;
+  int col_gi = 0;        // COLUMN: index of this wave's column group
+  bool active = true;    // COLUMN: the virtual tile may have fewer than 4 groups
+  int r0_w = 0;          // COLUMN: first row of the wave's column part
+  if (COLUMN) {
+    col_gi = 4 * vt + wave_s;
+    active = col_gi < ncol;
+    const int grp = col_list[min(col_gi, ncol - 1)];
+    kw0 = 64 * grp;
+    const int t1 = min((64 * grp / TK) * TK + TK - 1, N - 1);
+    r0_w = (lg_qtile_window_hi(m, t1, TQ) + 1) * TQ;
+  }
   const int j = kw0 + n;
 
   bf16x8_t kf[2][DC];
@@ -666,16 +729,23 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 #pragma unroll
   for (int i = 0; i < 16; ++i) lg_acc_zero(i, zero8);
 
-  int lo, hi;
-  const int hq0 = hk * G;
-  if (ncol > 0) {  // the window part; the column part is the COLUMN instance's
+  int lo, hi, hq0 = hk * G, nheads = G;
+  if (COLUMN) {  // one chunk of the rows after the window part of the virtual tile's first group
+    const int grp0 = col_list[4 * vt];
+    const int t1 = min((64 * grp0 / TK) * TK + TK - 1, N - 1);
+    lo = lg_qtile_window_hi(m, t1, TQ) + 1 + chunk * LG_COL_CHUNK;
+    hi = min((N - 1) / TQ, lo + LG_COL_CHUNK - 1);
+    if (lo > hi) return;
+    hq0 += gq;
+    nheads = 1;
+  } else if (ncol > 0) {  // the window part; the column part is the COLUMN instance's
     lo = k0 / TQ;
     hi = lg_qtile_window_hi(m, k1, TQ);
   } else {
     lg_qtile_range(m, k0, k1, TQ, &lo, &hi);
   }
   const int per_head = hi - lo + 1;
-  const int steps = per_head * G;
+  const int steps = per_head * nheads;
 
   Dma dma;
   dma.init(tid);
@@ -684,7 +754,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   const uint32_t lds0 = (uint32_t)(uintptr_t)LG_LDS_PTR(unsigned char, smem);
 #pragma unroll
   for (int x = 0; x < 4; ++x) {
-    const int r0 = k0 + 64 * x;
+    const int r0 = COLUMN ? 64 * col_list[min(4 * vt + x, ncol - 1)] : k0 + 64 * x;
     const int rc = min(r0, N - 1);  // a tile wholly past the end repeats the last row
     dma.issue(v + kbase + (size_t)rc * D, r0 < N ? N - r0 : 1, lds0 + x * T::BYTES);
   }
@@ -723,6 +793,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     const int q0 = u_c * TQ;
     u_c = (u_c == hi) ? lo : u_c + 1;
     const int q1 = min(q0 + TQ - 1, N - 1);
+    if (COLUMN && (!active || q0 < r0_w)) continue;  // no group, or rows of its window part
     const int kind = lg_tile_kind(m, q0, q1, kw0, kw0 + 63);
     if (kind == LG_TILE_DEAD) continue;
     const bool full = kind == LG_TILE_FULL && q0 + TQ <= N;
@@ -860,6 +931,23 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 
   // the last matrix results must have landed before the blocks are copied out
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  if (COLUMN) {  // partial sums of the column parts, as in the 8-wave kernel
+    float* tr = reinterpret_cast<float*>(smem + voff);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int nrows = active ? min(max(N - kw0 - 32 * kb, 0), 32) : 0;
+      const size_t prow = (((size_t)bh * ncol + col_gi) * 64 + kb * 32) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        float akv[16], avv[16];
+        lg_acc_get(kb * 4 + db, akv);
+        lg_acc_get(8 + kb * 4 + db, avv);
+        lg_atomic_add_block(tr, akv, part_dk + prow + db * 32, D, nrows, n, g);
+        lg_atomic_add_block(tr, avv, part_dv + prow + db * 32, D, nrows, n, g);
+      }
+    }
+    return;
+  }
   const int cid = (ncol > 0 && kw0 < N) ? col_of_group[kw0 >> 6] : -1;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
@@ -1259,16 +1347,23 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
       else LG_DKDV_LAUNCH(128, false, CC, GRID);        \
     }                                                   \
   } while (0)
+    // the 64-keys-per-wave kernel pays off once a key tile has a dozen or more query tiles
+    const bool wide = sh.D == 128 && (m.wb * m.b + LG_BF16_BTK) / LG_BF16_BTQ >= 16;
     if (cl.ncol > 0) {
       // list the column groups, clear their partial sums, run the column parts
       const long long ncolwg = (long long)((cl.ncol + 3) / 4) * cl.nchunk * sh.Hq * sh.B;
       if (ncolwg > 0x7fffffffLL) return hipErrorInvalidValue;
-      dkdv_column_table_kernel<<<1, 64, 0, s>>>(col_of_group, col_list, m, cl.ngroups);
+      dkdv_column_table_kernel<<<1, 1024, 0, s>>>(col_of_group, col_list, m, cl.ngroups);
       const size_t n4 = (cl.end - cl.pdk_off) / sizeof(float4);
       fill_zero_kernel<<<dim3((unsigned)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048)), 256, 0, s>>>(
           (float4*)pdk, n4);
       const dim3 grid_col((unsigned)ncolwg);
-      LG_DKDV_BOTH(true, grid_col);
+      if (wide)  // (column parts exist only with a stride: never the token instance)
+        dkdv_wide_bf16_kernel<false, true><<<grid_col, 256, 0, s>>>(
+            uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
+            per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
+      else
+        LG_DKDV_BOTH(true, grid_col);
       e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
@@ -1277,17 +1372,15 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     const dim3 grid_main(cl.ncol > 0 ? per_xcd * 8 : nbh + per_xcd_main * 8);
     {
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
-      // the 64-keys-per-wave kernel pays off once a key tile has a dozen or more query tiles
-      const int win_steps = (m.wb * m.b + LG_BF16_BTK) / LG_BF16_BTQ;
-      if (sh.D == 128 && win_steps >= 16) {
+      if (wide) {
         if (token)
-          dkdv_wide_bf16_kernel<true><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,
-                                                                (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-                                                                per_xcd, col_of_group, pdk, pdv, cl.ncol);
+          dkdv_wide_bf16_kernel<true, false><<<grid_main, 256, 0, s>>>(
+              uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
         else
-          dkdv_wide_bf16_kernel<false><<<grid_main, 256, 0, s>>>(uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk,
-                                                                 (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-                                                                 per_xcd, col_of_group, pdk, pdv, cl.ncol);
+          dkdv_wide_bf16_kernel<false, false><<<grid_main, 256, 0, s>>>(
+              uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
       } else {
         LG_DKDV_BOTH(false, grid_main);
       }

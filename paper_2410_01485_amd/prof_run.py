@@ -1,9 +1,10 @@
 """Run one entry point on one benchmark workload a few times, for rocprofv3.
 
     rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o NAME -- \
-        python3 paper_2410_01485_amd/prof_run.py {fwd|bwd|decode|fwd_strided|fwd_gqa|copy} [reps]
+        python3 paper_2410_01485_amd/prof_run.py {fwd|bwd|bwd_strided|decode|fwd_strided|fwd_gqa|copy} [reps]
 
 fwd / bwd   : B1 H32 D128 N131072 bf16, sink 64 + window 4096 (the training-step workload)
+bwd_strided : B1 H32 D128 N131072 bf16, 64-token blocks: sink block, window 2048, every 64th block
 fwd_strided : B1 H32 D128 N32768 bf16, 64-token blocks: own + 2 preceding, sink block, every 8th
 fwd_gqa     : B1 Hq64/Hkv8 D128 N131072 bf16, sink 64 + window 4096
 decode      : B16 H32 D128 bf16, 64 + 4096 cache slots, three rotating cache sets
@@ -35,18 +36,20 @@ def main():
         b = torch.empty_like(a)
         for _ in range(reps):
             torch.add(a, 1.0, out=b)   # an elementwise kernel: reads 2^30 bytes, writes 2^30 bytes
-    elif what in ("fwd", "bwd", "fwd_strided", "fwd_gqa"):
+    elif what in ("fwd", "bwd", "bwd_strided", "fwd_strided", "fwd_gqa"):
         Hq, Hkv, N, sink, window, block, stride = 32, 32, 131072, 64, 4096, 1, 0
         if what == "fwd_strided":
             N, sink, window, block, stride = 32768, 64, 192, 64, 8
         if what == "fwd_gqa":
             Hq, Hkv = 64, 8
+        if what == "bwd_strided":
+            sink, window, block, stride = 64, 2048, 64, 64
         D = 128
         q, k, v = rnd(1, Hq, N, D), rnd(1, Hkv, N, D), rnd(1, Hkv, N, D)
         out = torch.empty_like(q)
         lse = torch.empty(1, Hq, N, dtype=torch.float32, device=dev)
         lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window, block, stride)
-        if what == "bwd":
+        if what in ("bwd", "bwd_strided"):
             g = rnd(1, Hq, N, D)
             ws = torch.empty(lg.bwd_workspace_bytes(1, Hq, Hkv, N, D, sink, window, block, stride, lg.LG_BF16),
                              dtype=torch.uint8, device=dev)

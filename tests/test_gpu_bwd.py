@@ -98,13 +98,16 @@ def test_strided_columns_long_context(B, Hq, Hkv, N, D, sink, window, block, str
 @pytest.mark.parametrize("B,Hq,Hkv,N,D,sink,window,block,stride", [
     # windows of 16 or more tiles at D = 128 select the kernels with 64 query rows / 64 keys per wave:
     # token-granular with a ragged end (sink tile handled by the main instance); GQA with batch
-    # (column instance + partial sums folded into the main instance); block-granular; block-strided;
-    # no sink and a window longer than most rows
+    # (column instance + partial sums folded into the main instance); block-granular; block-strided
+    # (both instances in the 64-keys form); no sink and a window longer than most rows
     (1, 2, 2, 3001, 128, 64, 1024, 1, 0),
     (2, 4, 2, 2500, 128, 3, 900, 1, 0),
     (1, 2, 1, 3333, 128, 64, 1024, 64, 0),
     (1, 2, 2, 4100, 128, 64, 1024, 64, 8),
     (1, 1, 1, 2049, 128, 0, 2048, 1, 0),
+    # column instance of the 64-keys-per-wave kernel: 29 column groups (a last virtual tile of one), column
+    # parts longer than one chunk, GQA, ragged end
+    (1, 4, 2, 9000, 128, 64, 1024, 64, 5),
 ])
 def test_long_windows_wide_kernels(B, Hq, Hkv, N, D, sink, window, block, stride):
     check_bwd(B, Hq, Hkv, N, D, sink, window, block, stride, dtype=torch.bfloat16, seed=77)
@@ -183,6 +186,7 @@ def test_paper_block_settings_full_size_sampled():
     col = 63 * 64  # first strided column block
     for h, rows, keys in ((0, (0, 40), (20, 60)),                       # sink keys
                           (7, (70001, 70041), (col + 10, col + 50)),    # a strided column
+                          (11, (120000, 120040), (1087 * 64 + 10, 1087 * 64 + 50)),   # a strided column past 64-key group 1024
                           (19, (100000, 100040), (90010, 90050)),       # window-only keys
                           (31, (N - 40, N), (N - 40, N))):              # the end of the sequence
         print("head", h, "rows", rows, "keys", keys, flush=True)
