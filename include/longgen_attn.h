@@ -115,8 +115,8 @@ int lg_sparse_attn_fwd(const void* q, const void* k, const void* v, void* out, f
  *   Delta_i = <dout_i, out_i>;   dP_ij = <dout_i, v_j>;   dS_ij = P_ij (dP_ij - Delta_i)
  *   dq_i = scale * sum_j dS_ij k_j;   dk_j = scale * sum_i dS_ij q_i;   dv_j = sum_i P_ij dout_i
  * (sums over live pairs only; dk/dv also summed over the query heads of a kv head).
- * workspace holds Delta (float32 [B,Hq,N]), on the bf16 path also lse * log2(e) in the same
- * shape, and any float32 partial sums.  It must be ordinary device memory (hipMalloc /
+ * workspace holds per-row values (float32 [B,Hq,N]: Delta on the float32 path; -Delta and
+ * -lse / scale on the bf16 path) and any float32 partial sums.  It must be ordinary device memory (hipMalloc /
  * PyTorch): with a strided pattern or Hq > Hkv the bf16 path adds partial dk/dv sums of sink
  * and strided-column keys into it with hardware float atomics; their order is not fixed, so
  * the last bits of those dk/dv rows can differ between runs (a sink + window call with
