@@ -3,10 +3,9 @@
 //
 // Two kernels (the first one also forms Delta).  Sink + window without GQA uses no atomics and is
 // bit-reproducible; strided patterns and GQA add float32 partial dk/dv sums of the column keys
-// with atomics (see the dk/dv section).  Tiles
-// travel global -> LDS directly (row-major, swizzled; lg_swz.h) and are read both with the
-// contraction over dims (row reads) and with the contraction over tile rows (transposing
-// LDS reads), so no tile is ever stored twice.
+// with atomics (see the dk/dv section).  Tiles travel global -> LDS directly (row-major,
+// swizzled; lg_swz.h) and are read both with the contraction over dims (row reads) and with the
+// contraction over tile rows (transposing LDS reads), so no tile is ever stored twice.
 //
 //  dq kernel (query-tile major, same tile walk and 4-stage ring as the forward; 8 waves x
 //  32 query rows).  Per live key tile:
