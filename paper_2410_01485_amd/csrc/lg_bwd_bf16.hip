@@ -1357,7 +1357,9 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
       fill_zero_kernel<<<dim3((unsigned)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048)), 256, 0, s>>>(
           (float4*)pdk, n4);
       const dim3 grid_col((unsigned)ncolwg);
-      if (wide)  // (column parts exist only with a stride: never the token instance)
+      // column parts are long whatever the window is: the 64-keys form whenever it exists (its
+      // general-predicate instance serves token-granular patterns too)
+      if (sh.D == 128)
         dkdv_wide_bf16_kernel<false, true><<<grid_col, 256, 0, s>>>(
             uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
             per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
