@@ -1298,13 +1298,16 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
     const int total = (int)tl, per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8);
+    // key tiles of an average query tile: its window, plus the strided columns below it
+    const int col_tiles = m.stride > 0 ? (sh.N / 2) / (m.b * m.stride) * ((m.b + LG_BF16_TK - 1) / LG_BF16_TK) : 0;
+    const int key_tiles = (m.wb * m.b + LG_BF16_TQ) / LG_BF16_TK + col_tiles;
 #define LG_DQ_LAUNCH(DD, TT)                                                                        \
   dq_bf16_kernel<DD, TT><<<grid, 512, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq, \
                                               sh.Hkv, sh.scale, m, nqt, total, per_xcd)
     if (sh.D == 64) {
       if (token) LG_DQ_LAUNCH(64, true);
       else LG_DQ_LAUNCH(64, false);
-    } else if ((m.wb * m.b + LG_BF16_TQ) / LG_BF16_TK < 16) {
+    } else if (key_tiles < 16) {
       // few key tiles per query tile: the 8-wave kernel starts up and drains faster
       if (token) LG_DQ_LAUNCH(128, true);
       else LG_DQ_LAUNCH(128, false);
