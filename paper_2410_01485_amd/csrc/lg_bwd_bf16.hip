@@ -352,18 +352,21 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   //     (head, key tile) items follow in XCD-contiguous runs, so that neighbouring key tiles
   //     share their Q / dO rows in one XCD's L2.
   //   main, columns split off: all items in XCD-contiguous runs.
-  //   COLUMN: blockIdx.x = (((b x kv head) * G + query head of the group) * nvt + virtual tile)
-  //     * nchunk + chunk; chunks past the end of the range exit at once.
+  //   COLUMN: blockIdx.x = (chunk * nvt + virtual tile) * (heads) + (b x kv head) * G + query head of
+  //     the group: with the heads innermost every XCD gets the same mix of long and short items (and
+  //     of those that exit at once: a virtual tile has no rows in the chunks before its column part
+  //     starts), and the virtual tiles of one head that walk the same chunk of query rows run on one
+  //     XCD at about the same time.
   int bh, kt = 0, vt = 0, chunk = 0, gq = 0;
   if (COLUMN) {
-    const int nvt = (ncol + 3) / 4;
+    const int nvt = (ncol + 3) / 4, nh = (total / nkt) * G;
     int x = blockIdx.x;
-    chunk = x % nchunk;
-    x /= nchunk;
+    const int hd = x % nh;
+    x /= nh;
     vt = x % nvt;
-    x /= nvt;
-    gq = x % G;
-    bh = x / G;
+    chunk = x / nvt;
+    gq = hd % G;
+    bh = hd / G;
   } else if (ncol > 0) {
     const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (L >= total) return;
@@ -415,11 +418,16 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     for (int r = 0; r < 16; ++r) ak[db][r] = av[db][r] = 0.f;
   // query tiles of this work item
   int lo, hi, hq0 = hk * G, nheads = G;
-  if (COLUMN) {  // one chunk of the rows after the window part of the virtual tile's first group
+  if (COLUMN) {
+    // the query tiles of chunk number `chunk` (chunks are cut at fixed tile numbers for all virtual
+    // tiles, counted from the chunk in which the first column part starts) that come after the
+    // window part of the virtual tile's first group
+    const int tf = min((64 * col_list[0] / TK) * TK + TK - 1, N - 1);
+    const int c_abs = (lg_qtile_window_hi(m, tf, TQ) + 1) / LG_COL_CHUNK + chunk;
     const int grp0 = col_list[4 * vt];
     const int t1 = min((64 * grp0 / TK) * TK + TK - 1, N - 1);
-    lo = lg_qtile_window_hi(m, t1, TQ) + 1 + chunk * LG_COL_CHUNK;
-    hi = min((N - 1) / TQ, lo + LG_COL_CHUNK - 1);
+    lo = max(lg_qtile_window_hi(m, t1, TQ) + 1, c_abs * LG_COL_CHUNK);
+    hi = min((N - 1) / TQ, c_abs * LG_COL_CHUNK + LG_COL_CHUNK - 1);
     if (lo > hi) return;
     hq0 += gq;
     nheads = 1;
@@ -663,13 +671,14 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     const int nvt = (ncol + 3) / 4;
     // (the results of these divisions are pinned to scalar registers: the global->LDS copies take
     // their base addresses, which derive from them, as scalar operands)
+    const int nh = (total / nkt) * G;
     int x = blockIdx.x;
-    chunk = __builtin_amdgcn_readfirstlane(x % nchunk);
-    x /= nchunk;
+    const int hd = x % nh;
+    x /= nh;
     vt = __builtin_amdgcn_readfirstlane(x % nvt);
-    x /= nvt;
-    gq = __builtin_amdgcn_readfirstlane(x % G);
-    bh = __builtin_amdgcn_readfirstlane(x / G);
+    chunk = __builtin_amdgcn_readfirstlane(x / nvt);
+    gq = __builtin_amdgcn_readfirstlane(hd % G);
+    bh = __builtin_amdgcn_readfirstlane(hd / G);
   } else if (ncol > 0) {
     const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (L >= total) return;
@@ -729,11 +738,16 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   for (int i = 0; i < 16; ++i) lg_acc_zero(i, zero8);
 
   int lo, hi, hq0 = hk * G, nheads = G;
-  if (COLUMN) {  // one chunk of the rows after the window part of the virtual tile's first group
+  if (COLUMN) {
+    // the query tiles of chunk number `chunk` (chunks are cut at fixed tile numbers for all virtual
+    // tiles, counted from the chunk in which the first column part starts) that come after the
+    // window part of the virtual tile's first group
+    const int tf = min((64 * col_list[0] / TK) * TK + TK - 1, N - 1);
+    const int c_abs = (lg_qtile_window_hi(m, tf, TQ) + 1) / LG_COL_CHUNK + chunk;
     const int grp0 = col_list[4 * vt];
     const int t1 = min((64 * grp0 / TK) * TK + TK - 1, N - 1);
-    lo = lg_qtile_window_hi(m, t1, TQ) + 1 + chunk * LG_COL_CHUNK;
-    hi = min((N - 1) / TQ, lo + LG_COL_CHUNK - 1);
+    lo = max(lg_qtile_window_hi(m, t1, TQ) + 1, c_abs * LG_COL_CHUNK);
+    hi = min((N - 1) / TQ, c_abs * LG_COL_CHUNK + LG_COL_CHUNK - 1);
     if (lo > hi) return;
     hq0 += gq;
     nheads = 1;
@@ -1255,10 +1269,10 @@ ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t head_bytes
   if (c.ncol > 0) {  // the first group has the longest column part
     const int t0 = (first * 64 / LG_BF16_BTK) * LG_BF16_BTK;
     const int t1 = (t0 + LG_BF16_BTK - 1 < sh.N - 1) ? t0 + LG_BF16_BTK - 1 : sh.N - 1;
-    const int far = (sh.N - 1) / LG_BF16_BTQ - lg_qtile_window_hi(m, t1, LG_BF16_BTQ);
-    c.nchunk = (far + LG_COL_CHUNK - 1) / LG_COL_CHUNK;
+    const int first_tile = lg_qtile_window_hi(m, t1, LG_BF16_BTQ) + 1, last_tile = (sh.N - 1) / LG_BF16_BTQ;
+    c.nchunk = last_tile / LG_COL_CHUNK - first_tile / LG_COL_CHUNK + 1;  // chunks are cut at fixed tile numbers
   }
-  c.tab_off = head_bytes;  // after the per-row arrays (Delta, lse * log2(e))
+  c.tab_off = head_bytes;  // after the per-row arrays (-Delta, -lse / scale)
   const size_t tab = (((size_t)2 * c.ngroups * sizeof(int)) + 255) & ~(size_t)255;
   const size_t part = (size_t)sh.B * sh.Hkv * c.ncol * 64 * sh.D * sizeof(float);
   c.pdk_off = c.tab_off + (c.ncol > 0 ? tab : 0);
