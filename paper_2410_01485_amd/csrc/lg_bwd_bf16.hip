@@ -822,14 +822,8 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           const int lo_c = j + 32 * kb - q0 - 4 * g;
-          const unsigned w_eff = j + 32 * kb < m.sink ? 0x7fffffffu : (unsigned)m.window;
-          uint32_t w = 0;
-#pragma unroll 1
-          for (int r = 0; r < 32; ++r) {  // partial tiles are few: a plain loop keeps the code small
-            const int c = 32 * (r >> 4) + lg_crow(r & 15, 0);
-            w |= (uint32_t)((unsigned)(c - lo_c) < w_eff && c < n_c) << r;
-          }
-          bits[kb] = w;
+          const long long end = j + 32 * kb < m.sink ? (long long)n_c : (long long)lo_c + m.window;
+          bits[kb] = lg_reg_run(lo_c, (int)min(end, (long long)n_c));
         }
       } else {
 #pragma unroll
@@ -1141,11 +1135,7 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
         if (TOKEN) {
           // key = k0 + 4g + c: live if inside the window of row i, or a sink key not after i
           const int hi = i - k0 - 4 * g, lo = hi - (m.window - 1), se = m.sink - k0 - 4 * g;
-#pragma unroll 1
-          for (int r = 0; r < 32; ++r) {
-            const int c = 32 * (r >> 4) + lg_crow(r & 15, 0);
-            w |= (uint32_t)((unsigned)(c - lo) < (unsigned)m.window || (c < se && c <= hi)) << r;
-          }
+          w = lg_reg_run(lo, hi + 1) | lg_reg_run(-1, min(se, hi + 1));
         } else {
 #pragma unroll 1
           for (int r = 0; r < 32; ++r) w |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
