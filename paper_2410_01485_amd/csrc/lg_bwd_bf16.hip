@@ -631,13 +631,14 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
 // COLUMN: the instance for the split-off column parts, as in the 8-wave kernel: a virtual tile of
 // four 64-key column groups, one group per wave, one chunk of the query range per workgroup,
 // float32 atomics into the partial sums.
+// bid: the work item, numbered like the block ids of the 8-wave kernel's grid.
 template <bool TOKEN, bool COLUMN>
-__global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
+__device__ __forceinline__ void dkdv_wide_item(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m_in,
     int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
-    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
+    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk, const int bid) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -672,7 +673,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     // (the results of these divisions are pinned to scalar registers: the global->LDS copies take
     // their base addresses, which derive from them, as scalar operands)
     const int nh = (total / nkt) * G;
-    int x = blockIdx.x;
+    int x = bid;
     const int hd = x % nh;
     x /= nh;
     vt = __builtin_amdgcn_readfirstlane(x % nvt);
@@ -680,17 +681,17 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
     gq = __builtin_amdgcn_readfirstlane(hd % G);
     bh = __builtin_amdgcn_readfirstlane(hd / G);
   } else if (ncol > 0) {
-    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int L = (bid % 8) * per_xcd + bid / 8;
     if (L >= total) return;
     bh = L / nkt;
     kt = L % nkt;
   } else {
     const int nbh = total / nkt;
-    if ((int)blockIdx.x < nbh) {
-      bh = blockIdx.x;
+    if (bid < nbh) {
+      bh = bid;
       kt = 0;
     } else {
-      const int idx = blockIdx.x - nbh;
+      const int idx = bid - nbh;
       const int L = (idx % 8) * per_xcd + idx / 8;
       if (nkt == 1 || L >= total - nbh) return;
       bh = L / (nkt - 1);
@@ -992,6 +993,52 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
   }
 }
 
+// The column instance: one workgroup per work item.
+template <bool TOKEN, bool COLUMN>
+__global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m,
+    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
+    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk) {
+  dkdv_wide_item<TOKEN, COLUMN>(q, k, v, dout, nlse, ndelta, dk, dv, Hq, Hkv, scale, m, nkt, total, per_xcd,
+                                col_of_group, col_list, part_dk, part_dv, ncol, nchunk, (int)blockIdx.x);
+}
+
+// The main instance: a workgroup holds a whole CU (4 x 512 registers, 130 KB of LDS), so the launch of
+// the next one cannot overlap anything.  One workgroup per CU therefore stays and takes work items
+// from a queue: queue[x] counts the items handed out with id % 8 == x (ids with the same residue
+// are the ones that a grid launch would have placed on XCD x; a workgroup serves its own XCD's
+// ids first, then the others').  Every workgroup leaves once all eight counters have run out.
+template <bool TOKEN>
+__global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel_q(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const float* __restrict__ nlse, const float* __restrict__ ndelta,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int Hq, int Hkv, float scale, LgMask m,
+    int nkt, int total, int per_xcd, const int* __restrict__ col_of_group, const int* __restrict__ col_list,
+    float* __restrict__ part_dk, float* __restrict__ part_dv, int ncol, int nchunk, int* __restrict__ queue,
+    int nitems) {
+  __shared__ int s_item;
+  const int xcd = blockIdx.x & 7;
+  for (;;) {
+    __syncthreads();  // everyone is done with the previous item: its LDS, and s_item
+    if (threadIdx.x == 0) {
+      int id = -1;
+      for (int d = 0; d < 8 && id < 0; ++d) {
+        const int x = (xcd + d) & 7;
+        const int c = atomicAdd(queue + x, 1);
+        if (c < (1 << 27) && 8 * c + x < nitems) id = 8 * c + x;
+      }
+      s_item = id;
+    }
+    __syncthreads();
+    const int id = __builtin_amdgcn_readfirstlane(s_item);
+    if (id < 0) return;
+    dkdv_wide_item<TOKEN, false>(q, k, v, dout, nlse, ndelta, dk, dv, Hq, Hkv, scale, m, nkt, total, per_xcd,
+                                 col_of_group, col_list, part_dk, part_dv, ncol, nchunk, id);
+  }
+}
+
 // ------------------------------------------------- dq: 64 query rows per wave (D = 128)
 // Same idea as the wide dk/dv kernel: four waves of 64 query rows, so that every K / V operand
 // read from LDS feeds two matrix instructions; same tile walk as the 8-wave kernel, the 4-stage ring
@@ -1239,7 +1286,7 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
 namespace {
 struct ColumnLayout {
   int nkt, ngroups, ncol, nchunk;  // ncol = 0: no column parts are split off
-  size_t tab_off, pdk_off, pdv_off, end;
+  size_t tab_off, pdk_off, pdv_off, queue_off, end;
 };
 ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t head_bytes) {
   ColumnLayout c;
@@ -1267,7 +1314,8 @@ ColumnLayout column_layout(const LgShape& sh, const LgMask& m, size_t head_bytes
   const size_t part = (size_t)sh.B * sh.Hkv * c.ncol * 64 * sh.D * sizeof(float);
   c.pdk_off = c.tab_off + (c.ncol > 0 ? tab : 0);
   c.pdv_off = c.pdk_off + part;
-  c.end = c.pdv_off + part;
+  c.queue_off = (c.pdv_off + part + 255) & ~(size_t)255;  // the work queue's counters (8 ints)
+  c.end = c.queue_off + 256;
   return c;
 }
 }  // namespace
@@ -1381,14 +1429,23 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     {
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
       if (wide) {
+        // one resident workgroup per CU, work items (the ids of grid_main) from a queue
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+          return hipErrorInvalidDevice;
+        int* queue = (int*)((char*)ws + cl.queue_off);
+        const int nitems = (int)grid_main.x;
+        const dim3 grid_q((unsigned)(nitems < cus ? nitems : cus));
+        fill_zero_kernel<<<1, 64, 0, s>>>((float4*)queue, 2);
         if (token)
-          dkdv_wide_bf16_kernel<true, false><<<grid_main, 256, 0, s>>>(
+          dkdv_wide_bf16_kernel_q<true><<<grid_q, 256, 0, s>>>(
               uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue, nitems);
         else
-          dkdv_wide_bf16_kernel<false, false><<<grid_main, 256, 0, s>>>(
+          dkdv_wide_bf16_kernel_q<false><<<grid_q, 256, 0, s>>>(
               uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk);
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue, nitems);
       } else {
         LG_DKDV_BOTH(false, grid_main);
       }
