@@ -618,6 +618,26 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   }
 }
 
+// Work queue of the kernels that keep one workgroup per CU: queue[x] counts the items handed out
+// with id % 8 == x (the ids that a grid launch would have placed on XCD x); a workgroup serves its
+// own XCD's ids first, then the others'.  Returns the next id, or -1 once all eight counters have
+// run out (every wave of every workgroup gets there).  Called by all threads of the workgroup; the
+// barriers also separate two items' use of LDS.
+__device__ __forceinline__ int lg_queue_take(int* __restrict__ queue, int nitems, int xcd, int* s_item) {
+  __syncthreads();  // everyone is done with the previous item: its LDS, and *s_item
+  if (threadIdx.x == 0) {
+    int id = -1;
+    for (int d = 0; d < 8 && id < 0; ++d) {
+      const int x = (xcd + d) & 7;
+      const int c = atomicAdd(queue + x, 1);
+      if (c < (1 << 27) && 8 * c + x < nitems) id = 8 * c + x;
+    }
+    *s_item = id;
+  }
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(*s_item);
+}
+
 // ------------------------------------------------- dk, dv: 64 keys per wave (D = 128)
 // The main instance for D = 128.  Four waves of 64 keys each: every operand read from LDS (Q / dO
 // rows, their transposed blocks) now feeds two matrix instructions, which halves the LDS traffic
@@ -1007,9 +1027,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel(
 
 // The main instance: a workgroup holds a whole CU (4 x 512 registers, 130 KB of LDS), so the launch of
 // the next one cannot overlap anything.  One workgroup per CU therefore stays and takes work items
-// from a queue: queue[x] counts the items handed out with id % 8 == x (ids with the same residue
-// are the ones that a grid launch would have placed on XCD x; a workgroup serves its own XCD's
-// ids first, then the others').  Every workgroup leaves once all eight counters have run out.
+// from a queue (lg_queue_take).
 template <bool TOKEN>
 __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel_q(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -1021,18 +1039,7 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel_q(
   __shared__ int s_item;
   const int xcd = blockIdx.x & 7;
   for (;;) {
-    __syncthreads();  // everyone is done with the previous item: its LDS, and s_item
-    if (threadIdx.x == 0) {
-      int id = -1;
-      for (int d = 0; d < 8 && id < 0; ++d) {
-        const int x = (xcd + d) & 7;
-        const int c = atomicAdd(queue + x, 1);
-        if (c < (1 << 27) && 8 * c + x < nitems) id = 8 * c + x;
-      }
-      s_item = id;
-    }
-    __syncthreads();
-    const int id = __builtin_amdgcn_readfirstlane(s_item);
+    const int id = lg_queue_take(queue, nitems, xcd, &s_item);
     if (id < 0) return;
     dkdv_wide_item<TOKEN, false>(q, k, v, dout, nlse, ndelta, dk, dv, Hq, Hkv, scale, m, nkt, total, per_xcd,
                                  col_of_group, col_list, part_dk, part_dv, ncol, nchunk, id);
@@ -1046,12 +1053,13 @@ __global__ __launch_bounds__(256) void dkdv_wide_bf16_kernel_q(
 // accumulators (blocks 0..7 = a[0:127]: row block rb, dim block db -> block 4 rb + db) and the
 // wave's Q and dO fragments (a[128:255], four registers per 32 rows x 16 dims), which the matrix
 // instructions read as their second operand straight from there.
+// bid: the work item, numbered like the block ids of the 8-wave kernel's grid.
 template <bool TOKEN>
-__global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
+__device__ __forceinline__ void dq_wide_item(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ out, const uint16_t* __restrict__ dout, const float* __restrict__ lse,
     float* __restrict__ ndelta, float* __restrict__ nlse, uint16_t* __restrict__ dq, int Hq, int Hkv, float scale,
-    LgMask m_in, int nqt, int total, int per_xcd) {
+    LgMask m_in, int nqt, int total, int per_xcd, const int bid) {
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -1071,7 +1079,7 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
   constexpr int STAGE = 2 * T::BYTES;  // K tile + V tile
   __shared__ __attribute__((aligned(1024))) unsigned char smem[STAGES * STAGE];
 
-  const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int L = (bid % 8) * per_xcd + bid / 8;
   if (L >= total) return;
   const int G = Hq / Hkv;
   const int gq = L % G, rest = L / G;
@@ -1279,6 +1287,22 @@ __global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
   }
 }
 
+// One resident workgroup per CU that takes its work items from a queue, as the dk/dv kernel above.
+template <bool TOKEN>
+__global__ __launch_bounds__(256) void dq_wide_bf16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ out, const uint16_t* __restrict__ dout, const float* __restrict__ lse,
+    float* __restrict__ ndelta, float* __restrict__ nlse, uint16_t* __restrict__ dq, int Hq, int Hkv, float scale,
+    LgMask m, int nqt, int total, int per_xcd, int* __restrict__ queue, int nitems) {
+  __shared__ int s_item;
+  const int xcd = blockIdx.x & 7;
+  for (;;) {
+    const int id = lg_queue_take(queue, nitems, xcd, &s_item);
+    if (id < 0) return;
+    dq_wide_item<TOKEN>(q, k, v, out, dout, lse, ndelta, nlse, dq, Hq, Hkv, scale, m, nqt, total, per_xcd, id);
+  }
+}
+
 }  // namespace
 
 // Workspace of the bf16 backward after Delta: two int tables of nkt entries, then the float32
@@ -1344,6 +1368,17 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
   const uint16_t* uv = (const uint16_t*)v;
   const uint16_t* ug = (const uint16_t*)dout;
   const bool token = m.b == 1 && m.stride == 0;
+  const ColumnLayout cl = column_layout(sh, m, 2 * row_bytes);
+  // the work queues of the kernels that keep one workgroup per CU: 8 counters each, cleared per call
+  int* queue = (int*)((char*)ws + cl.queue_off);
+  int cus = 0;
+  {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      return hipErrorInvalidDevice;
+    fill_zero_kernel<<<1, 64, 0, s>>>((float4*)queue, 4);
+  }
   {
     const int nqt = (sh.N + LG_BF16_TQ - 1) / LG_BF16_TQ;
     const long long tl = (long long)nqt * sh.Hq * sh.B;
@@ -1363,12 +1398,15 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
       // few key tiles per query tile: the 8-wave kernel starts up and drains faster
       if (token) LG_DQ_LAUNCH(128, true);
       else LG_DQ_LAUNCH(128, false);
-    } else if (token) {
-      dq_wide_bf16_kernel<true><<<grid, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
-                                                     sh.Hkv, sh.scale, m, nqt, total, per_xcd);
     } else {
-      dq_wide_bf16_kernel<false><<<grid, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
-                                                      sh.Hkv, sh.scale, m, nqt, total, per_xcd);
+      const int nitems = (int)grid.x;
+      const dim3 grid_q((unsigned)(nitems < cus ? nitems : cus));
+      if (token)
+        dq_wide_bf16_kernel<true><<<grid_q, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
+                                                         sh.Hkv, sh.scale, m, nqt, total, per_xcd, queue, nitems);
+      else
+        dq_wide_bf16_kernel<false><<<grid_q, 256, 0, s>>>(uq, uk, uv, uo, ug, lse, ndelta, nlse, (uint16_t*)dq, sh.Hq,
+                                                          sh.Hkv, sh.scale, m, nqt, total, per_xcd, queue, nitems);
     }
 #undef LG_DQ_LAUNCH
     e = hipGetLastError();
@@ -1376,7 +1414,6 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     if (ev) (void)hipEventRecord(ev[2], s);
   }
   {
-    const ColumnLayout cl = column_layout(sh, m, 2 * row_bytes);
     const int nkt = cl.nkt;
     const long long tl = (long long)nkt * sh.Hkv * sh.B;
     if (tl > 0x7fffffffLL - 8) return hipErrorInvalidValue;
@@ -1429,23 +1466,17 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
     {
       const int per_xcd = per_xcd_main;  // the value the kernel's mapping expects
       if (wide) {
-        // one resident workgroup per CU, work items (the ids of grid_main) from a queue
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-          return hipErrorInvalidDevice;
-        int* queue = (int*)((char*)ws + cl.queue_off);
+        // one resident workgroup per CU, work items (the ids of grid_main) from the second queue
         const int nitems = (int)grid_main.x;
         const dim3 grid_q((unsigned)(nitems < cus ? nitems : cus));
-        fill_zero_kernel<<<1, 64, 0, s>>>((float4*)queue, 2);
         if (token)
           dkdv_wide_bf16_kernel_q<true><<<grid_q, 256, 0, s>>>(
               uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue, nitems);
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue + 8, nitems);
         else
           dkdv_wide_bf16_kernel_q<false><<<grid_q, 256, 0, s>>>(
               uq, uk, uv, ug, nlse, ndelta, (uint16_t*)dk, (uint16_t*)dv, sh.Hq, sh.Hkv, sh.scale, m, nkt, total,
-              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue, nitems);
+              per_xcd, col_of_group, col_list, pdk, pdv, cl.ncol, cl.nchunk, queue + 8, nitems);
       } else {
         LG_DKDV_BOTH(false, grid_main);
       }
