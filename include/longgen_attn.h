@@ -116,7 +116,8 @@ int lg_sparse_attn_fwd(const void* q, const void* k, const void* v, void* out, f
  *   dq_i = scale * sum_j dS_ij k_j;   dk_j = scale * sum_i dS_ij q_i;   dv_j = sum_i P_ij dout_i
  * (sums over live pairs only; dk/dv also summed over the query heads of a kv head).
  * workspace holds per-row values (float32 [B,Hq,N]: Delta on the float32 path; -Delta and
- * -lse / scale on the bf16 path) and any float32 partial sums.  It must be ordinary device memory (hipMalloc /
+ * -lse / scale on the bf16 path), any float32 partial sums and, on the bf16 path, the counters
+ * of the kernels' work queues (cleared by every call).  It must be ordinary device memory (hipMalloc /
  * PyTorch): with a strided pattern or Hq > Hkv the bf16 path adds partial dk/dv sums of sink
  * and strided-column keys into it with hardware float atomics; their order is not fixed, so
  * the last bits of those dk/dv rows can differ between runs (a sink + window call with
