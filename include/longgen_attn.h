@@ -117,7 +117,8 @@ int lg_sparse_attn_fwd(const void* q, const void* k, const void* v, void* out, f
  * (sums over live pairs only; dk/dv also summed over the query heads of a kv head).
  * workspace holds per-row values (float32 [B,Hq,N]: Delta on the float32 path; -Delta and
  * -lse / scale on the bf16 path), any float32 partial sums and, on the bf16 path, the counters
- * of the kernels' work queues (cleared by every call).  It must be ordinary device memory (hipMalloc /
+ * of the kernels' work queues (cleared by every call).  A workspace belongs to one call at a
+ * time: two calls that may overlap (different streams) need a workspace each.  It must be ordinary device memory (hipMalloc /
  * PyTorch): with a strided pattern or Hq > Hkv the bf16 path adds partial dk/dv sums of sink
  * and strided-column keys into it with hardware float atomics; their order is not fixed, so
  * the last bits of those dk/dv rows can differ between runs (a sink + window call with
