@@ -8,8 +8,10 @@ One step = the training pass of one sparse layer on the Llama-2-7B-shaped 128K w
 backward (dq kernel, which also forms Delta, and dk/dv kernel), inputs resident in HBM.  The headline
 value is effective TFLOP/s: algorithmic flops of the live (query, key) pairs (4*D forward,
 10*D backward per pair per head) divided by the measured step time.  The same run also times
-decode over the 64+4096-slot ring cache (B16, 32 heads) and the fp64 CPU oracle on a bounded
-sample.  Prints ONE JSON line.
+decode over the 64+4096-slot ring cache (B16, 32 heads), the other workloads of the benchmark set
+(float32 correctness config, block-strided forward at 32K, GQA forward at 128K), the paper's block-granular
+settings, a 32-layer attention-only stack (12 full + 20 sparse layers, executed call by call) against 32 full
+layers, and the fp64 CPU oracle on a bounded sample.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -93,26 +95,30 @@ def main():
     for _ in range(W):
         step()
     torch.cuda.synchronize()
-    # The timed region: K steps.  The backward goes through the library's timing variant of the
-    # same entry point: identical kernels, bracketed by HIP events on the launch stream, so the
-    # per-kernel durations below come from exactly the launches that are timed.  (It waits for
-    # its last event before returning; that host gap, tens of microseconds, is inside step_ms.)
+    # The timed region: K steps through the product entry points (lg_sparse_attn_fwd, lg_sparse_attn_bwd),
+    # bracketed by events on the stream the binding hands to the library (torch's current stream).
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
-    split = [0.0, 0.0, 0.0]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(K):
         ev[s][0].record()
         lg.lg_sparse_attn_fwd(q, k, v, out, lse, sink, window)
         ev[s][1].record()
-        ms = lg.lg_debug_bwd_kernel_ms(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window)
+        lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window)
         ev[s][2].record()
-        split = [a + b / K for a, b in zip(split, ms)]
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / K
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
     step_ms = ev[0][0].elapsed_time(ev[-1][2]) / K
     per_step = sorted(e[0].elapsed_time(e[2]) for e in ev)
+    # The split of the backward over its kernels: a separate, untimed pass of K calls of the library's timing
+    # variant of the same entry point (identical launches, each kernel bracketed by HIP events on the launch
+    # stream; it synchronises after every call, which is why it is not what the timed region runs).
+    split = [0.0, 0.0, 0.0]
+    for _ in range(K):
+        ms = lg.lg_debug_bwd_kernel_ms(q, k, v, out, lse, g, dq, dk, dv, ws, sink, window)
+        split = [a + b / K for a, b in zip(split, ms)]
 
     pairs = live_pairs(N, sink, window) * H * B
     fl_fwd, fl_bwd = 4.0 * D * pairs, 10.0 * D * pairs
@@ -134,7 +140,7 @@ def main():
                 "avg_launch_ms": dom["ms"],
                 "kernels": [{"kernel": x["kernel"], "ms": round(x["ms"], 4), "tflops": round(x["tflops"], 1),
                              "frac": round(x["frac"], 4)} for x in kernels],
-                "delta_prepass_ms": round(split[0], 4),
+                "bwd_setup_ms": round(split[0], 4),  # clearing the work-queue counters (Delta is formed in the dq kernel)
                 "fwd": {"ms": round(fwd_ms, 4), "tflops": round(fl_fwd / fwd_ms / 1e9, 1),
                         "frac": round(fl_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS, 4)},
                 "bwd": {"ms": round(bwd_ms, 4), "tflops": round(fl_bwd / bwd_ms / 1e9, 1),
@@ -167,32 +173,114 @@ def main():
                       "tflops": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12, 1),
                       "frac": round(14.0 * D * pp / ((f_ms + b_ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
         del pws
-    # full causal attention through the same kernels (window >= N), one launch after a warm-up: the
-    # cost of a full-attention layer at this length, and what a 12 full + 20 sparse layer stack
-    # (the paper's hybrid) saves on attention alone
+    # Full causal attention through the same kernels (window >= N) and the paper's hybrid as an executed
+    # attention-only stack (Section 3.1: 32 layers, sparse attention in the bottom 10 and top 10 layers, full
+    # attention in the middle 12): 32 consecutive layer calls on one stream, each layer's output feeding the
+    # next layer's queries (forward) and each layer's dq feeding the layer below as its upstream gradient
+    # (backward, reverse order), timed end to end, beside the same stack with 32 full layers.
     full = None
     if not args.no_extras:
+        L_ALL = 32
+        hybrid = [i < 10 or i >= 22 for i in range(L_ALL)]          # True = sparse layer
         fws = torch.empty(lg.bwd_workspace_bytes(B, H, H, N, D, 0, N, 1, 0, lg.LG_BF16), dtype=torch.uint8,
                           device=dev)
+        # per-layer activations kept for the backward: queries (= the previous layer's out), out, lse
+        acts = [q] + [torch.empty_like(q) for _ in range(L_ALL)]
+        lses = [torch.empty_like(lse) for _ in range(L_ALL)]
+        grads = [torch.empty_like(q), torch.empty_like(q)]
+
+        def stack_fwd(sparse_layers):
+            for i in range(L_ALL):
+                sk_, w_ = (sink, window) if sparse_layers[i] else (0, N)
+                lg.lg_sparse_attn_fwd(acts[i], k, v, acts[i + 1], lses[i], sk_, w_)
+
+        def stack_bwd(sparse_layers):
+            gin = g
+            for i in reversed(range(L_ALL)):
+                sk_, w_ = (sink, window) if sparse_layers[i] else (0, N)
+                gout = grads[i & 1]
+                lg.lg_sparse_attn_bwd(acts[i], k, v, acts[i + 1], lses[i], gin, gout, dk, dv,
+                                      ws if sparse_layers[i] else fws, sk_, w_)
+                gin = gout
+
+        def timed(fn, *a):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            fn(*a)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1)
+
+        # warm-up: one full-causal layer forward and backward (the sparse kernels ran above)
         lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
-        torch.cuda.synchronize()
-        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        e0.record()
-        lg.lg_sparse_attn_fwd(q, k, v, out, lse, 0, N)
-        e1.record()
         lg.lg_sparse_attn_bwd(q, k, v, out, lse, g, dq, dk, dv, fws, 0, N)
-        e2.record()
-        torch.cuda.synchronize()
-        cf, cb = e0.elapsed_time(e1), e1.elapsed_time(e2)
+        cf = timed(lg.lg_sparse_attn_fwd, q, k, v, out, lse, 0, N)
+        cb = timed(lg.lg_sparse_attn_bwd, q, k, v, out, lse, g, dq, dk, dv, fws, 0, N)
+        all_full = [False] * L_ALL
+        hyb_fwd = timed(stack_fwd, hybrid)
+        hyb_bwd = timed(stack_bwd, hybrid)
+        ful_fwd = timed(stack_fwd, all_full)
+        ful_bwd = timed(stack_bwd, all_full)
         cpairs = N * (N + 1) // 2 * H * B
-        full = {"workload": "full causal attention, same shape (window = N)", "fwd_ms": round(cf, 2),
-                "bwd_ms": round(cb, 2), "tflops": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12, 1),
-                "attention_speedup_12_full_20_sparse_vs_32_full": {
-                    "train": round(32 * (cf + cb) / (12 * (cf + cb) + 20 * step_ms), 2),
-                    "prefill": round(32 * cf / (12 * cf + 20 * fwd_ms), 2)}}
-        del fws
+        full = {"workload": "full causal attention, same shape (window = N), one layer",
+                "fwd_ms": round(cf, 2), "bwd_ms": round(cb, 2),
+                "tflops": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12, 1),
+                "frac": round(14.0 * D * cpairs / ((cf + cb) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "stack_32_layers_executed": {
+                    "what": "attention-only stack, 32 consecutive layer calls per pass on one stream: hybrid = 10 "
+                            "sparse + 12 full + 10 sparse layers (sink 64 + window 4096), against 32 full layers; "
+                            "the paper's end-to-end figures (1.55x training, 1.67x prefill, whole model, A100s) "
+                            "include the linear layers and are context only",
+                    "hybrid_prefill_ms": round(hyb_fwd, 1), "all_full_prefill_ms": round(ful_fwd, 1),
+                    "hybrid_train_ms": round(hyb_fwd + hyb_bwd, 1), "all_full_train_ms": round(ful_fwd + ful_bwd, 1),
+                    "attention_speedup_prefill": round(ful_fwd / hyb_fwd, 2),
+                    "attention_speedup_train": round((ful_fwd + ful_bwd) / (hyb_fwd + hyb_bwd), 2)}}
+        del fws, acts, lses, grads
     del q, k, v, g, out, lse, dq, dk, dv, ws
     torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ the other workloads of the benchmark set
+    # (forward only, as their definitions say): the float32 correctness config, the block-strided forward at
+    # 32K and the GQA forward at 128K.  5 launches each after 2 warm-ups, events around the product call.
+    PEAK_F32_VECTOR_TFLOPS = 157.3
+    others = []
+    if not args.no_extras:
+        def fwd_config(name, what, Bc, Hq, Hkv, Nc, Dc, dt, sk_, w_, blk, st_, seed, pairs_per_head, extra):
+            cq, ck, cv = lg_synth.prefill_inputs(Bc, Hq, Hkv, Nc, Dc, seed, dt, device=dev)
+            co = torch.empty_like(cq)
+            cl = torch.empty(Bc, Hq, Nc, dtype=torch.float32, device=dev)
+            for _ in range(2):
+                lg.lg_sparse_attn_fwd(cq, ck, cv, co, cl, sk_, w_, blk, st_)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(5):
+                lg.lg_sparse_attn_fwd(cq, ck, cv, co, cl, sk_, w_, blk, st_)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            fl = 4.0 * Dc * pairs_per_head * Hq * Bc
+            peak = PEAK_BF16_TFLOPS if dt == torch.bfloat16 else PEAK_F32_VECTOR_TFLOPS
+            rec = {"config": name, "workload": what, "fwd_ms": round(ms, 4), "flops": fl,
+                   "tflops": round(fl / (ms * 1e-3) / 1e12, 3), "peak_tflops": peak,
+                   "frac": round(fl / (ms * 1e-3) / 1e12 / peak, 4), "live_pairs_per_head": pairs_per_head}
+            rec.update(extra)
+            others.append(rec)
+
+        fwd_config("config 1", "B1 H1 N1024 D64 float32, sink 16 + window 128 (correctness config: one small "
+                   "launch, latency-bound; priced against the float32 vector peak)", 1, 1, 1, 1024, 64,
+                   torch.float32, 16, 128, 1, 0, 20241002, live_pairs(1024, 16, 128), {"bound": "alu"})
+        nblk = 32768 // 64
+        live_blocks = sum(len(set(range(min(1, qb))) | set(range(max(0, qb - 2), qb + 1)) | set(range(7, qb, 8)))
+                          for qb in range(nblk))
+        fwd_config("config 2", "B1 H32/32 N32768 D128 bf16, 64-token blocks: own block + 2 preceding, sink block, "
+                   "every 8th earlier block", 1, 32, 32, 32768, 128, torch.bfloat16, 64, 192, 64, 8, 20241003,
+                   block_pairs(32768, 64, 192, 64, 8),
+                   {"bound": "mfma", "live_blocks_per_head": live_blocks, "causal_blocks_per_head": nblk * (nblk + 1) // 2})
+        fwd_config("config 4", "B1 Hq64/Hkv8 (GQA) N131072 D128 bf16, sink 64 + window 4096", 1, 64, 8, 131072, 128,
+                   torch.bfloat16, 64, 4096, 1, 0, 20241005, live_pairs(131072, 64, 4096), {"bound": "mfma"})
+        torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ decode, ring cache
     dB, dH, dsink, dwin, dN = 16, 32, 64, 4096, 131072
@@ -305,8 +393,8 @@ def main():
                    "wall_ms_per_step": round(wall_ms, 3),
                    "ms_per_step_median": round(per_step[len(per_step) // 2], 3),
                    "ms_per_step_min": round(per_step[0], 3)},
-        "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "paper_block_settings": paper,
-        "full_causal": full,
+        "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": others,
+        "paper_block_settings": paper, "full_causal": full,
     }))
 
 

@@ -136,8 +136,13 @@ int lg_sparse_attn_bwd(const void* q, const void* k, const void* v, const void* 
 /*
  * Measurement aid (benchmarks only): lg_sparse_attn_bwd with each of its three kernels
  * bracketed by HIP events on hip_stream.  Synchronises the stream and writes the kernel
- * durations in milliseconds to the HOST array kernel_ms[3] = {Delta pre-pass, dq kernel,
- * dk/dv kernel}.  Creates and destroys its events; results are those of lg_sparse_attn_bwd.
+ * durations in milliseconds to the HOST array kernel_ms[3] = {set-up, dq, dk/dv}:
+ *   set-up  float32 path: the Delta pre-pass kernel; bf16 path: the kernel that clears the work-queue
+ *           counters (a few microseconds: on that path Delta is formed inside the dq kernel)
+ *   dq      the dq kernel
+ *   dk/dv   the dk/dv kernel and, for strided patterns and GQA, what precedes it: the column-table
+ *           kernel, the clearing of the partial sums and the column instance
+ * Creates and destroys its events; results are those of lg_sparse_attn_bwd.
  */
 int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const void* out, const float* lse,
                            const void* dout, void* dq, void* dk, void* dv,
@@ -214,8 +219,9 @@ int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* 
  *                      token); values outside [1, n_max] are clamped
  *   positions        : [B] int32 device, position of the first of the T new tokens per sequence
  * n_max bounds the context lengths: pages_per_seq * page_size >= lg_kv_cache_slots(n_max, ...)
- * is required, and the workspace is sized for it.  Page numbers are not checked on the device:
- * every entry a sequence can reach must be < num_pages.
+ * is required, and the workspace is sized for it.  Every table entry a sequence can reach must be
+ * in [0, num_pages); an entry outside that range is clamped into it on the device (the result of that
+ * sequence is then wrong, but nothing outside the pool is read or written).
  * lg_kv_paged_append stores k_new, v_new [B, Hkv, T, D]; a strided-block copy whose slot lies
  * beyond pages_per_seq pages is dropped.
  */

@@ -30,8 +30,12 @@ def build(force=False):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        # LG_ORACLE_LIB: load this build of lg_oracle.c instead (the sanitizer test points it at a copy
+        # compiled with -fsanitize=address,undefined)
+        alt = os.environ.get("LG_ORACLE_LIB")
+        if not alt:
+            build()
+        L = ctypes.CDLL(alt or _LIB)
         lng, dbl = ctypes.c_long, ctypes.c_double
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)

@@ -9,7 +9,8 @@ import os
 
 LG_F32, LG_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblonggen_attn.so")
+# LONGGEN_ATTN_LIB: path of another build of the same library (e.g. one with sanitized host code)
+_LIB_PATH = os.environ.get("LONGGEN_ATTN_LIB") or os.path.join(_HERE, "liblonggen_attn.so")
 _lib = None
 
 _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
@@ -98,18 +99,38 @@ def _stream(t):
     return torch.cuda.current_stream(t.device).cuda_stream
 
 
-def _check(t, *shape):
+def _check(t, *shape, like=None, dtype=None):
+    """t must be a contiguous device tensor of this shape; like / dtype: of that tensor's / that element type
+    (the library reads every buffer of a call with the one dtype code it is given)."""
     if not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
         raise ValueError("expected a contiguous device tensor of shape %s, got %s" % (shape, tuple(t.shape)))
+    want = like.dtype if like is not None else dtype
+    if want is not None and t.dtype != want:
+        raise TypeError("expected dtype %s, got %s" % (want, t.dtype))
+
+
+def _check_lse(lse, *shape):
+    import torch
+    _check(lse, *shape, dtype=torch.float32)
+
+
+def _ws_bytes(workspace):
+    """Size of a workspace tensor (None: 0); it must live on the device."""
+    if workspace is None:
+        return 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("the workspace must be a contiguous device tensor")
+    return workspace.numel() * workspace.element_size()
 
 
 def lg_sparse_attn_fwd(q, k, v, out, lse, sink, window, block=1, stride=0, scale=0.0):
     """out, lse <- sparse attention forward of q [B,Hq,N,D], k,v [B,Hkv,N,D]; lse may be None."""
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
-    _check(q, B, Hq, N, D), _check(k, B, Hkv, N, D), _check(v, B, Hkv, N, D), _check(out, B, Hq, N, D)
+    _check(q, B, Hq, N, D), _check(k, B, Hkv, N, D, like=q), _check(v, B, Hkv, N, D, like=q)
+    _check(out, B, Hq, N, D, like=q)
     if lse is not None:
-        _check(lse, B, Hq, N)
+        _check_lse(lse, B, Hq, N)
     st = lib().lg_sparse_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, Hq, Hkv, N, D,
                                   sink, window, block, stride, _dtype_code(q), scale, _stream(q))
     if st != 0:
@@ -126,13 +147,12 @@ def lg_sparse_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink, win
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
     for t in (q, out, dout, dq):
-        _check(t, B, Hq, N, D)
+        _check(t, B, Hq, N, D, like=q)
     for t in (k, v, dk, dv):
-        _check(t, B, Hkv, N, D)
-    _check(lse, B, Hq, N)
+        _check(t, B, Hkv, N, D, like=q)
+    _check_lse(lse, B, Hq, N)
     st = lib().lg_sparse_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
-                                  _ptr(dk), _ptr(dv), _ptr(workspace),
-                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  _ptr(dk), _ptr(dv), _ptr(workspace), _ws_bytes(workspace),
                                   B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
                                   _stream(q))
     if st != 0:
@@ -145,9 +165,13 @@ def lg_debug_bwd_kernel_ms(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink,
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
     ms = (_f * 3)()
+    for t in (q, out, dout, dq):
+        _check(t, B, Hq, N, D, like=q)
+    for t in (k, v, dk, dv):
+        _check(t, B, Hkv, N, D, like=q)
+    _check_lse(lse, B, Hq, N)
     st = lib().lg_debug_bwd_kernel_ms(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
-                                      _ptr(dk), _ptr(dv), _ptr(workspace),
-                                      workspace.numel() * workspace.element_size(),
+                                      _ptr(dk), _ptr(dv), _ptr(workspace), _ws_bytes(workspace),
                                       B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
                                       _stream(q), ms)
     if st != 0:
@@ -164,12 +188,12 @@ def lg_sparse_attn_decode(q, k_cache, v_cache, out, lse, workspace, N, sink, win
     """out, lse <- one-token attention of q [B,Hq,D] over caches [B,Hkv,sink+window,D]."""
     B, Hq, D = q.shape
     Hkv = k_cache.shape[1]
-    _check(k_cache, B, Hkv, sink + window, D), _check(v_cache, B, Hkv, sink + window, D), _check(out, B, Hq, D)
+    _check(q, B, Hq, D), _check(k_cache, B, Hkv, sink + window, D, like=q)
+    _check(v_cache, B, Hkv, sink + window, D, like=q), _check(out, B, Hq, D, like=q)
     if lse is not None:
-        _check(lse, B, Hq)
+        _check_lse(lse, B, Hq)
     st = lib().lg_sparse_attn_decode(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
-                                     _ptr(workspace),
-                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _ptr(workspace), _ws_bytes(workspace),
                                      B, Hq, Hkv, N, D, sink, window, block, stride, _dtype_code(q), scale,
                                      _stream(q))
     if st != 0:
@@ -205,12 +229,12 @@ def lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, workspace, N, sin
     """out, lse <- one-token attention of q [B,Hq,D] over caches [B,Hkv,slots,D] of any pattern."""
     B, Hq, D = q.shape
     Hkv, slots = k_cache.shape[1], k_cache.shape[2]
-    _check(k_cache, B, Hkv, slots, D), _check(v_cache, B, Hkv, slots, D), _check(out, B, Hq, D)
+    _check(q, B, Hq, D), _check(k_cache, B, Hkv, slots, D, like=q), _check(v_cache, B, Hkv, slots, D, like=q)
+    _check(out, B, Hq, D, like=q)
     if lse is not None:
-        _check(lse, B, Hq)
+        _check_lse(lse, B, Hq)
     st = lib().lg_sparse_attn_decode_cache(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
-                                           _ptr(workspace),
-                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                           _ptr(workspace), _ws_bytes(workspace),
                                            B, Hq, Hkv, N, D, sink, window, block, stride, slots, _dtype_code(q),
                                            scale, _stream(q))
     if st != 0:
@@ -235,13 +259,13 @@ def lg_sparse_attn_decode_paged(q, k_pages, v_pages, page_table, seq_lens, out, 
     seq_lens [B] int32 on the device."""
     B, Hq, D = q.shape
     num_pages, Hkv, page_size = k_pages.shape[0], k_pages.shape[1], k_pages.shape[2]
-    _check(k_pages, num_pages, Hkv, page_size, D), _check(v_pages, num_pages, Hkv, page_size, D), _check(out, B, Hq, D)
+    _check(q, B, Hq, D), _check(k_pages, num_pages, Hkv, page_size, D, like=q)
+    _check(v_pages, num_pages, Hkv, page_size, D, like=q), _check(out, B, Hq, D, like=q)
     _check_i32(page_table, B, page_table.shape[1]), _check_i32(seq_lens, B)
     if lse is not None:
-        _check(lse, B, Hq)
+        _check_lse(lse, B, Hq)
     st = lib().lg_sparse_attn_decode_paged(_ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(seq_lens),
-                                           _ptr(out), _ptr(lse), _ptr(workspace),
-                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                           _ptr(out), _ptr(lse), _ptr(workspace), _ws_bytes(workspace),
                                            B, Hq, Hkv, n_max, D, sink, window, block, stride, page_size,
                                            page_table.shape[1], num_pages, _dtype_code(q), scale, _stream(q))
     if st != 0:
@@ -253,8 +277,8 @@ def lg_kv_paged_append(k_new, v_new, k_pages, v_pages, page_table, positions, n_
     """Store k_new, v_new [B,Hkv,T,D] (sequence b: positions[b] .. +T-1) into the paged caches in place."""
     B, Hkv, T, D = k_new.shape
     num_pages, page_size = k_pages.shape[0], k_pages.shape[2]
-    _check(v_new, B, Hkv, T, D), _check(k_new, B, Hkv, T, D)
-    _check(k_pages, num_pages, Hkv, page_size, D), _check(v_pages, num_pages, Hkv, page_size, D)
+    _check(v_new, B, Hkv, T, D, like=k_new), _check(k_new, B, Hkv, T, D)
+    _check(k_pages, num_pages, Hkv, page_size, D, like=k_new), _check(v_pages, num_pages, Hkv, page_size, D, like=k_new)
     _check_i32(page_table, B, page_table.shape[1]), _check_i32(positions, B)
     st = lib().lg_kv_paged_append(_ptr(k_new), _ptr(v_new), _ptr(k_pages), _ptr(v_pages), _ptr(page_table),
                                   _ptr(positions), B, Hkv, D, T, n_max, sink, window, block, stride, page_size,
@@ -316,7 +340,10 @@ def lg_debug_decode_split_headdim(q, k_cache, v_cache, out, lse, N, sink, window
     import torch
     B, Hq, D = q.shape
     Hkv = k_cache.shape[1]
-    _check(k_cache, B, Hkv, sink + window, D), _check(v_cache, B, Hkv, sink + window, D), _check(out, B, Hq, D)
+    _check(q, B, Hq, D), _check(k_cache, B, Hkv, sink + window, D, like=q)
+    _check(v_cache, B, Hkv, sink + window, D, like=q), _check(out, B, Hq, D, like=q)
+    if lse is not None:
+        _check_lse(lse, B, Hq)
     need = int(lib().lg_debug_decode_split_headdim_workspace_bytes(B, Hq, sink, window))
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     st = lib().lg_debug_decode_split_headdim(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(ws),

@@ -21,16 +21,28 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose=True, jobs=8):
-    """Compile every translation unit (in parallel) and link the shared library."""
-    objdir = os.path.join(HERE, "_build")
+# host code (argument checks, host build of the tile scheduler, launch set-up) under AddressSanitizer and
+# UndefinedBehaviorSanitizer; the device code is built as usual
+SAN_COMPILE = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+               "-Xarch_host", "-fno-sanitize-recover=undefined"]
+SAN_LINK = ["-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"]
+
+
+def build(verbose=True, jobs=8, sanitize_host=False, out=None):
+    """Compile every translation unit (in parallel) and link the shared library.
+
+    sanitize_host: build a second library (path `out`) whose HOST code runs under ASan + UBSan; a process
+    that loads it must have the clang ASan runtime preloaded (tests/test_sanitized_host.py does that)."""
+    lib = out or LIB
+    objdir = os.path.join(HERE, "_build_san" if sanitize_host else "_build")
     os.makedirs(objdir, exist_ok=True)
+    flags = FLAGS + (SAN_COMPILE if sanitize_host else [])
     procs = []
     objs = []
     for src in sources():
         obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
-        cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+        cmd = [HIPCC] + flags + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
@@ -47,13 +59,13 @@ def build(verbose=True, jobs=8):
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + (SAN_LINK if sanitize_host else []) + ["-o", tmp] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -96,7 +96,10 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* out
   hipEvent_t* ev = nullptr;
   if (kernel_ms) {
     for (int x = 0; x < 4; ++x)
-      if (hipEventCreate(&evs[x]) != hipSuccess) return LG_ERR_LAUNCH;
+      if (hipEventCreate(&evs[x]) != hipSuccess) {
+        while (x > 0) (void)hipEventDestroy(evs[--x]);  // the ones created so far
+        return LG_ERR_LAUNCH;
+      }
     ev = evs;
   }
   hipError_t e = (dtype == LG_F32)
@@ -256,7 +259,7 @@ int lg_sparse_attn_decode_paged(const void* q, const void* k_pages, const void* 
   const LgShape sh = make_shape(B, Hq, Hkv, n_max, D, scale);
   hipError_t e = lg_launch_decode(q, k_pages, v_pages, out, lse, workspace, B, Hq, Hkv, 0, g, D, dtype, sh.scale,
                                   static_cast<hipStream_t>(hip_stream), page_table, seq_lens, pages_per_seq,
-                                  page_shift, n_max, &cm);
+                                  page_shift, n_max, &cm, num_pages);
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
 }
 
@@ -279,7 +282,7 @@ int lg_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void
   const LgMask m = lg_make_cache_mask(n_max, sink, window, block, stride);
   const int row_bytes = D * (dtype == LG_F32 ? 4 : 2);
   hipError_t e = lg_launch_kv_paged_append(k_new, v_new, k_pages, v_pages, page_table, positions, B, Hkv,
-                                           row_bytes, T, pages_per_seq, page_shift, m,
+                                           row_bytes, T, pages_per_seq, page_shift, num_pages, m,
                                            static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
 }

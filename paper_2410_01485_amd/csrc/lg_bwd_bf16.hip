@@ -920,6 +920,21 @@ __device__ __forceinline__ void dkdv_wide_item(
     auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
 
     // two copies of the step: tiles that are live throughout skip the mask tests
+    // Instruction numbers inside a 64-instruction block (see the table above): the chains' last
+    // instructions, the anchors, and the first instruction after which each group of 8 pieces runs.
+    constexpr int S_LAST = 15, DP_LAST = 31, C_FIRST = 32, D_FIRST = 48, NEXT_S = 64;
+    constexpr int TIE_S = S_LAST + LG_MFMA_GAP, TIE_DP = DP_LAST + LG_MFMA_GAP;
+    constexpr int P0 = 22, P1 = 32, DS0 = 40, DS1 = 48, NP = 8;  // P h0, P h1, dS h0, dS h1: NP pieces each
+    static_assert(lg_readable_after(TIE_S, S_LAST) && P0 > TIE_S && P1 > TIE_S, "P reads S too early");
+    static_assert(lg_readable_after(TIE_DP, DP_LAST) && DS0 > TIE_DP && DS1 > TIE_DP, "dS reads dP too early");
+    static_assert(DS0 >= P0 + NP && DS1 >= P1 + NP, "dS of a half needs its P");
+    // piece x of a group serves key block (x / 4) % 2; instruction C_FIRST + 8 h + 2 c' + kb reads the P of
+    // (kb, h), D_FIRST + ... the dS: the last piece of key block 0 is number 3, of key block 1 number 7
+    static_assert(lg_operand_ready(C_FIRST, P0 + 3) && lg_operand_ready(C_FIRST + 1, P0 + 7), "P (h0) late for dV");
+    static_assert(lg_operand_ready(C_FIRST + 8, P1 + 3) && lg_operand_ready(C_FIRST + 9, P1 + 7), "P (h1) late for dV");
+    static_assert(lg_operand_ready(D_FIRST, DS0 + 3) && lg_operand_ready(D_FIRST + 1, DS0 + 7), "dS (h0) late for dK");
+    static_assert(lg_operand_ready(D_FIRST + 8, DS1 + 3) && lg_operand_ready(D_FIRST + 9, DS1 + 7), "dS (h1) late for dK");
+    static_assert(DS1 + NP <= NEXT_S, "the vector work of a block ends before the next block's S overwrites it");
     auto run_step = [&](auto MASKED) {
     constexpr bool masked = decltype(MASKED)::value;
     __builtin_amdgcn_sched_barrier(0);
@@ -940,16 +955,16 @@ __device__ __forceinline__ void dkdv_wide_item(
       } else {
         lg_acc_fma(4 * kb + (c & 3), ra[sl], bop(wD[kb][c >> 2]));
       }
-      if (mm == 21) lg_tie(sc[0], sc[1]);
-      if (mm == 37) lg_tie(dp[0], dp[1]);
+      if (mm == TIE_S) lg_tie(sc[0], sc[1]);
+      if (mm == TIE_DP) lg_tie(dp[0], dp[1]);
       if (mm == 8) row_init(sL + 64, q);             // -Delta rows: dP starts at 16
       if (m == 56) row_init(sL, 1);                  // -lse / scale rows of the second block
       __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
       // pieces: P h0 at 22..29, P h1 at 32..39, dS h0 at 40..47, dS h1 at 48..55; key block = bit 2
-      if (mm >= 22 && mm < 30) sm_piece(masked, q, ((mm - 22) >> 2) & 1, 0, (mm - 22) & 3);
-      if (mm >= 32 && mm < 40) sm_piece(masked, q, ((mm - 32) >> 2) & 1, 1, (mm - 32) & 3);
-      if (mm >= 40 && mm < 48) ds_piece(((mm - 40) >> 2) & 1, 0, (mm - 40) & 3);
-      if (mm >= 48 && mm < 56) ds_piece(((mm - 48) >> 2) & 1, 1, (mm - 48) & 3);
+      if (mm >= P0 && mm < P0 + NP) sm_piece(masked, q, ((mm - P0) >> 2) & 1, 0, (mm - P0) & 3);
+      if (mm >= P1 && mm < P1 + NP) sm_piece(masked, q, ((mm - P1) >> 2) & 1, 1, (mm - P1) & 3);
+      if (mm >= DS0 && mm < DS0 + NP) ds_piece(((mm - DS0) >> 2) & 1, 0, (mm - DS0) & 3);
+      if (mm >= DS1 && mm < DS1 + NP) ds_piece(((mm - DS1) >> 2) & 1, 1, (mm - DS1) & 3);
       __builtin_amdgcn_sched_barrier(0);
     });
     };
@@ -1236,6 +1251,20 @@ __device__ __forceinline__ void dq_wide_item(
     };
     auto bop = [&](const uint32_t* w) { return lg_as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])); };
 
+    // Instruction numbers of the tile (see the table above): last instruction of each chain, anchors, first
+    // instruction after which each group of 16 pieces runs.
+    constexpr int S0_LAST = 15, DP0_LAST = 31, S1_LAST = 47, DP1_LAST = 63, E0_FIRST = 64, E1_FIRST = 80;
+    constexpr int TIE_S0 = S0_LAST + LG_MFMA_GAP, TIE_DP0 = DP0_LAST + LG_MFMA_GAP, TIE_S1 = S1_LAST + LG_MFMA_GAP,
+                  TIE_DP1 = DP1_LAST + LG_MFMA_GAP;
+    constexpr int PP0 = 22, DSS0 = 38, PP1 = 54, DSS1 = 70, NPC = 16;
+    static_assert(lg_readable_after(TIE_S0, S0_LAST) && PP0 > TIE_S0, "P(0) reads S too early");
+    static_assert(lg_readable_after(TIE_DP0, DP0_LAST) && DSS0 > TIE_DP0 && DSS0 >= PP0 + NPC, "dS(0) too early");
+    static_assert(lg_readable_after(TIE_S1, S1_LAST) && PP1 > TIE_S1, "P(1) reads S too early");
+    static_assert(lg_readable_after(TIE_DP1, DP1_LAST) && DSS1 > TIE_DP1 && DSS1 >= PP1 + NPC, "dS(1) too early");
+    // pieces 0..7 of a dS group are h = 0 (both row blocks), 8..15 are h = 1; E(kb) reads h = 0 in its first
+    // eight instructions and h = 1 in its last eight
+    static_assert(lg_operand_ready(E0_FIRST, DSS0 + 7) && lg_operand_ready(E0_FIRST + 8, DSS0 + 15), "dS(0) late for dQ");
+    static_assert(lg_operand_ready(E1_FIRST, DSS1 + 7) && lg_operand_ready(E1_FIRST + 8, DSS1 + 15), "dS(1) late for dQ");
     auto run_tile = [&](auto MASKED) {
       constexpr bool masked = decltype(MASKED)::value;
       __builtin_amdgcn_sched_barrier(0);
@@ -1250,15 +1279,15 @@ __device__ __forceinline__ void dq_wide_item(
         else if (ph == 1 || ph == 3) lg_frag_mfma(16 + 8 * rb + c, false, dp[kb][rb], ra[sl]);
         else lg_acc_fma(4 * rb + (c & 3), ra[sl], bop(wD[kb][rb][c >> 2]));
         // S / dP are final six matrix instructions after their last one
-        if (mi == 21) lg_tie(sc[0][0], sc[0][1]);
-        if (mi == 37) lg_tie(dp[0][0], dp[0][1]);
-        if (mi == 53) lg_tie(sc[1][0], sc[1][1]);
-        if (mi == 69) lg_tie(dp[1][0], dp[1][1]);
+        if (mi == TIE_S0) lg_tie(sc[0][0], sc[0][1]);
+        if (mi == TIE_DP0) lg_tie(dp[0][0], dp[0][1]);
+        if (mi == TIE_S1) lg_tie(sc[1][0], sc[1][1]);
+        if (mi == TIE_DP1) lg_tie(dp[1][0], dp[1][1]);
         __builtin_amdgcn_sched_barrier(0);  // the piece follows its matrix instruction
-        if (mi >= 22 && mi < 38) p_piece(masked, 0, mi - 22);
-        if (mi >= 38 && mi < 54) ds_piece(0, mi - 38);
-        if (mi >= 54 && mi < 70) p_piece(masked, 1, mi - 54);
-        if (mi >= 70 && mi < 86) ds_piece(1, mi - 70);
+        if (mi >= PP0 && mi < PP0 + NPC) p_piece(masked, 0, mi - PP0);
+        if (mi >= DSS0 && mi < DSS0 + NPC) ds_piece(0, mi - DSS0);
+        if (mi >= PP1 && mi < PP1 + NPC) p_piece(masked, 1, mi - PP1);
+        if (mi >= DSS1 && mi < DSS1 + NPC) ds_piece(1, mi - DSS1);
         __builtin_amdgcn_sched_barrier(0);
       });
     };
@@ -1358,10 +1387,10 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
   const size_t row_bytes = (((size_t)sh.B * sh.Hq * sh.N * sizeof(float)) + 255) & ~(size_t)255;
   float* ndelta = (float*)ws;
   float* nlse = (float*)((char*)ws + row_bytes);
-  // (no separate pre-pass on this path: the dq kernel forms Delta and writes both arrays)
+  // (no separate pre-pass on this path: the dq kernel forms Delta and writes both arrays; the first
+  // bracket of the timing aid holds only the kernel that clears the work-queue counters)
   if (ev) (void)hipEventRecord(ev[0], s);
   hipError_t e = hipSuccess;
-  if (ev) (void)hipEventRecord(ev[1], s);
   const uint16_t* uo = (const uint16_t*)out;
   const uint16_t* uq = (const uint16_t*)q;
   const uint16_t* uk = (const uint16_t*)k;
@@ -1378,6 +1407,7 @@ hipError_t lg_launch_bwd_bf16(const void* q, const void* k, const void* v, const
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       return hipErrorInvalidDevice;
     fill_zero_kernel<<<1, 64, 0, s>>>((float4*)queue, 4);
+    if (ev) (void)hipEventRecord(ev[1], s);
   }
   {
     const int nqt = (sh.N + LG_BF16_TQ - 1) / LG_BF16_TQ;

@@ -95,7 +95,7 @@ __device__ __forceinline__ void store_out(__hip_bfloat16* p, float x) { *p = __f
 struct LgPaged {
   const int* page_table;  // [B, pages_per_seq]
   const int* seq_lens;    // [B]
-  int pages_per_seq, page_shift, n_max;
+  int pages_per_seq, page_shift, n_max, num_pages;
   LgMask cm;              // cache geometry (lg_make_cache_mask), N filled in per sequence
 };
 
@@ -167,7 +167,9 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(const T* __restrict_
       }
       size_t off = (size_t)slot * D;
       if (MODE == LG_DEC_PAGED) {
-        const int page = pg.page_table[(size_t)b * pg.pages_per_seq + (slot >> pg.page_shift)];
+        // (a table entry outside the pool is clamped into it: a wrong result, never a stray read)
+        const int page = min(max(pg.page_table[(size_t)b * pg.pages_per_seq + (slot >> pg.page_shift)], 0),
+                             pg.num_pages - 1);
         off = ((((size_t)page * Hkv + hk) << pg.page_shift) + (slot & ((1 << pg.page_shift) - 1))) * D;
       }
       Frag<T, E>::load(kbase + off, kf[u]);
@@ -321,7 +323,8 @@ __global__ __launch_bounds__(256) void lg_kv_paged_append_kernel(const uint4* __
                                                                  uint4* __restrict__ kp, uint4* __restrict__ vp,
                                                                  const int* __restrict__ page_table,
                                                                  const int* __restrict__ positions, int T,
-                                                                 int pages_per_seq, int page_shift, LgMask m) {
+                                                                 int pages_per_seq, int page_shift, int num_pages,
+                                                                 LgMask m) {
   const int ti = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
   if (ti >= T) return;
   const int c = threadIdx.x % LPR;
@@ -331,7 +334,8 @@ __global__ __launch_bounds__(256) void lg_kv_paged_append_kernel(const uint4* __
   const int pos = max(positions[b], 0);
   const int p = pos + ti, last = pos + T - 1;
   auto put = [&](int slot) {
-    const int page = page_table[(size_t)b * pages_per_seq + (slot >> page_shift)];
+    // (a table entry outside the pool is clamped into it: a misplaced row, never a stray write)
+    const int page = min(max(page_table[(size_t)b * pages_per_seq + (slot >> page_shift)], 0), num_pages - 1);
     const size_t row = (((size_t)page * Hkv + hk) << page_shift) + (slot & ((1 << page_shift) - 1));
     kp[row * LPR + c] = kx;
     vp[row * LPR + c] = vx;
@@ -507,7 +511,8 @@ size_t lg_decode_workspace_bytes(int B, int Hq, int Hkv, int D, int valid) {
 hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void* out, float* lse,
                             void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
                             int dtype, float scale, hipStream_t s, const int* page_table, const int* seq_lens,
-                            int pages_per_seq, int page_shift, int n_max, const LgMask* cache_mask) {
+                            int pages_per_seq, int page_shift, int n_max, const LgMask* cache_mask,
+                            int num_pages) {
   LgPaged pg = {};
   const LgPaged* pp = nullptr;
   if (page_table) {
@@ -516,6 +521,7 @@ hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void*
     pg.pages_per_seq = pages_per_seq;
     pg.page_shift = page_shift;
     pg.n_max = n_max;
+    pg.num_pages = num_pages;
     pg.cm = *cache_mask;
     pp = &pg;
   }
@@ -545,8 +551,8 @@ hipError_t lg_launch_decode_split_headdim(const void* q, const void* kc, const v
 
 hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
                                      const int* page_table, const int* positions, int B, int Hkv,
-                                     int row_bytes, int T, int pages_per_seq, int page_shift, const LgMask& m,
-                                     hipStream_t s) {
+                                     int row_bytes, int T, int pages_per_seq, int page_shift, int num_pages,
+                                     const LgMask& m, hipStream_t s) {
   const int lpr = row_bytes / 16;
   const dim3 grid((T + 256 / lpr - 1) / (256 / lpr), Hkv, B);
   const uint4* kn = (const uint4*)k_new;
@@ -554,7 +560,7 @@ hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void*
   uint4* kp = (uint4*)k_pages;
   uint4* vp = (uint4*)v_pages;
 #define LG_PA(L) lg_kv_paged_append_kernel<L><<<grid, 256, 0, s>>>(kn, vn, kp, vp, page_table, positions, T, \
-                                                                   pages_per_seq, page_shift, m)
+                                                                   pages_per_seq, page_shift, num_pages, m)
   if (lpr == 8) LG_PA(8);
   else if (lpr == 16) LG_PA(16);
   else LG_PA(32);

@@ -54,15 +54,15 @@ hipError_t lg_launch_decode(const void* q, const void* kc, const void* vc, void*
                             void* ws, int B, int Hq, int Hkv, int C, const LgDecSegs& segs, int D,
                             int dtype, float scale, hipStream_t s, const int* page_table = nullptr,
                             const int* seq_lens = nullptr, int pages_per_seq = 0, int page_shift = 0,
-                            int n_max = 0, const LgMask* cache_mask = nullptr);
+                            int n_max = 0, const LgMask* cache_mask = nullptr, int num_pages = 0);
 size_t lg_decode_split_headdim_workspace_bytes(int B, int Hq, int C);
 hipError_t lg_launch_decode_split_headdim(const void* q, const void* kc, const void* vc, void* out, float* lse,
                                           void* ws, int B, int Hq, int Hkv, int C, int valid, int D, int dtype,
                                           float scale, hipStream_t s);
 hipError_t lg_launch_kv_paged_append(const void* k_new, const void* v_new, void* k_pages, void* v_pages,
                                      const int* page_table, const int* positions, int B, int Hkv,
-                                     int row_bytes, int T, int pages_per_seq, int page_shift, const LgMask& m,
-                                     hipStream_t s);
+                                     int row_bytes, int T, int pages_per_seq, int page_shift, int num_pages,
+                                     const LgMask& m, hipStream_t s);
 hipError_t lg_launch_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                                int B, int Hkv, int row_bytes, int T, int pos, int slots,
                                const LgMask& m, hipStream_t s);

@@ -86,10 +86,20 @@ __device__ __forceinline__ void lg_mfma_vi(f32x16_t& c, bf16x8_t a, bf16x8_t b, 
 // complete a few issue slots before the matrix instruction that reads them: the pieces that produce
 // P / dS end at least one matrix instruction earlier, the zero operand is followed by idle slots.
 // Program-order anchor without an instruction: everything that reads x or y is placed after this
-// point, everything that wrote them before it.  A vector instruction may read a matrix result
-// only ~20 issue slots after the matrix instruction was issued; the anchors are set where at
-// least four later matrix instructions (32 slots) lie in between.
+// point, everything that wrote them before it.  A vector instruction may read the result of an 8-pass
+// matrix instruction only 11 issue slots after that instruction was issued, and neither the hardware nor the
+// compiler (which does not look inside the statements) waits for it.  Four later matrix instructions
+// guarantee those slots whatever the state of the pipe; the unrolled steps keep LG_MFMA_GAP = 6, as
+// compile-time assertions on the instruction indices (lg_readable_after), and tests/test_build_isa.py checks
+// the distance in the generated code.
 __device__ __forceinline__ void lg_tie(f32x16_t& x, f32x16_t& y) { asm volatile("" : "+v"(x), "+v"(y)); }
+constexpr int LG_MFMA_GAP = 6;
+// Vector code placed after matrix instruction number `reader` of an unrolled step may read what
+// instruction number `last_writer` (the last of an accumulation chain) wrote.
+constexpr bool lg_readable_after(int reader, int last_writer) { return reader >= last_writer + LG_MFMA_GAP; }
+// A matrix instruction number `consumer` may read an operand that the vector piece placed after
+// instruction number `last_piece` completed: at least one whole matrix instruction lies in between.
+constexpr bool lg_operand_ready(int consumer, int last_piece) { return consumer >= last_piece + 2; }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
 template <int... I, typename F>

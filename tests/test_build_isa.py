@@ -135,3 +135,55 @@ def test_matrix_operands_are_not_written_just_before_use(wide_kernels):
                 if op.startswith("v_permlane32_swap") and len(ops) > 1:
                     for r in _regs(ops[1]):
                         written[r] = line
+
+
+MFMA_GAP = 4       # matrix instructions that must lie between an inline matrix instruction and a reader of its result
+NOP_STATES = 11    # ... or this many idle issue slots (what an 8-pass matrix instruction needs before a vector access)
+
+
+def _all_regs(text):
+    """Every VGPR / AGPR a piece of operand text names: ('v', n) / ('a', n)."""
+    regs = set()
+    for kind, lo, hi in re.findall(r"\b([va])\[(\d+):(\d+)\]", text):
+        regs |= {(kind, r) for r in range(int(lo), int(hi) + 1)}
+    for kind, n in re.findall(r"\b([va])(\d+)\b", text):
+        regs.add((kind, int(n)))
+    return regs
+
+
+def test_matrix_results_are_not_touched_too_early(wide_kernels):
+    """The other direction of the hazard: a vector or memory instruction that reads (or overwrites) a register
+    an inline matrix instruction wrote must come at least MFMA_GAP matrix instructions (or NOP_STATES idle
+    slots) later; the hardware does not wait for it and the compiler does not see inside the statement.  The
+    kernels place such readers six matrix instructions after the last one of an accumulation chain; this checks
+    the generated code (straight-line order, which is how the unrolled steps run).  A matrix instruction that
+    continues a chain on the same destination is exempt (the pipe forwards its own accumulator)."""
+    kernels, _, _ = wide_kernels
+    for name, body in kernels.items():
+        written = {}              # register -> (matrix instructions issued, idle slots) when a matrix instruction wrote it
+        n_mfma = n_nop = 0
+        for raw in body.splitlines():
+            line = raw.split(";")[0].strip()
+            if not line or line.startswith(".") or line.endswith(":"):
+                continue
+            op = line.split()[0]
+            rest = line.split(None, 1)[1] if " " in line else ""
+            if op.startswith("v_mfma"):
+                ops = [o.strip() for o in rest.split(",")]
+                dst = _all_regs(ops[0])
+                for r in (_all_regs(ops[1]) | _all_regs(ops[2])) & set(written):   # results are never fed back as A / B
+                    raise AssertionError(f"{name}: {line} reads {r} written by a matrix instruction")
+                if _all_regs(ops[3]) != dst:                                        # not a chain on its own accumulator
+                    for r in _all_regs(ops[3]) & set(written):
+                        w = written[r]
+                        assert n_mfma - w[0] >= MFMA_GAP or n_nop - w[1] >= NOP_STATES, f"{name}: {line} (addend {r})"
+                n_mfma += 1
+                for r in dst:
+                    written[r] = (n_mfma, n_nop)
+            elif op == "s_nop":
+                n_nop += int(rest.strip()) + 1
+            elif op.startswith(("v_", "ds_", "global_", "buffer_", "scratch_", "flat_")):
+                for r in _all_regs(rest) & set(written):
+                    w = written.pop(r)
+                    assert n_mfma - w[0] >= MFMA_GAP or n_nop - w[1] >= NOP_STATES, \
+                        f"{name}: {line} touches {r} {n_mfma - w[0]} matrix instructions after it was written"

@@ -8,7 +8,7 @@ import torch
 
 import lg_synth
 import paper_2410_01485_amd as lg
-from gpu_util import DEV, TOL_LSE, TOL_OUT, assert_close, f32np
+from gpu_util import DEV, TOL_LSE, TOL_OUT, TOL_REL, assert_close, f32np
 from oracle import lg_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -98,7 +98,7 @@ def test_decode_over_cache_equals_last_prefill_row(dtype, N, sink, window, block
     out, lse = decode_cache(q[:, :, N - 1].contiguous().to(DEV), kc, vc, N, sink, window, block, stride)
     wo, wl = O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(N - 1, N))
     tag = "decode_cache N%d s%d w%d b%d st%d %s" % (N, sink, window, block, stride, dtype)
-    assert_close(f32np(out), wo[:, :, N - 1], TOL_OUT[dtype], None, tag + " out")
+    assert_close(f32np(out), wo[:, :, N - 1], TOL_OUT[dtype], TOL_REL[dtype], tag + " out")
     assert_close(f32np(lse), wl[:, :, N - 1], TOL_LSE[dtype], None, tag + " lse")
 
 
@@ -118,7 +118,7 @@ def test_generation_loop_block_strided():
         lg.lg_kv_ring_append(kd[:, :, t:t + 1].contiguous(), vd[:, :, t:t + 1].contiguous(), kc, vc, t, sink, window,
                              block, stride)
         out, lse = decode_cache(qd[:, :, t].contiguous(), kc, vc, t + 1, sink, window, block, stride)
-        assert_close(f32np(out), wo[:, :, t], TOL_OUT[torch.bfloat16], None, "step %d out" % t)
+        assert_close(f32np(out), wo[:, :, t], TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16], "step %d out" % t)
         assert_close(f32np(lse), wl[:, :, t], TOL_LSE[torch.bfloat16], None, "step %d lse" % t)
 
 
@@ -134,7 +134,7 @@ def test_paper_settings_full_context(sink, window, block, stride):
     assert np.array_equal(bits(kc), wk) and np.array_equal(bits(vc), wv)
     out, lse = decode_cache(q[:, :, N - 1].contiguous().to(DEV), kc, vc, N, sink, window, block, stride)
     wo, wl = O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(N - 1, N))
-    assert_close(f32np(out), wo[:, :, N - 1], TOL_OUT[torch.bfloat16], None, "paper setting out")
+    assert_close(f32np(out), wo[:, :, N - 1], TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16], "paper setting out")
     assert_close(f32np(lse), wl[:, :, N - 1], TOL_LSE[torch.bfloat16], None, "paper setting lse")
 
 
@@ -192,7 +192,7 @@ def test_paged_varlen_decode(dtype, sink, window, block, stride, page_size):
                             window, block, stride)
     for b, ((q, k, v), n) in enumerate(zip(ctx, lens)):
         wo, wl = O.fwd(f32np(q), f32np(k), f32np(v), sink, window, block, stride, rows=(n - 1, n))
-        assert_close(f32np(out[b]), wo[0, :, n - 1], TOL_OUT[dtype], None, "paged seq %d out" % b)
+        assert_close(f32np(out[b]), wo[0, :, n - 1], TOL_OUT[dtype], TOL_REL[dtype], "paged seq %d out" % b)
         assert_close(f32np(lse[b]), wl[0, :, n - 1], TOL_LSE[dtype], None, "paged seq %d lse" % b)
 
 
@@ -219,5 +219,5 @@ def test_paged_generation_step_all_sequences_at_once():
         out, lse = paged_decode([q[0, :, p] for (q, _, _), p in zip(ctx, pos)], kp, vp, table, [p + 1 for p in pos],
                                 n_max, sink, window, block, stride)
         for b, p in enumerate(pos):
-            assert_close(f32np(out[b]), want[b][0][0, :, p], TOL_OUT[dtype], None, "step %d seq %d out" % (s, b))
+            assert_close(f32np(out[b]), want[b][0][0, :, p], TOL_OUT[dtype], TOL_REL[dtype], "step %d seq %d out" % (s, b))
             assert_close(f32np(lse[b]), want[b][1][0, :, p], TOL_LSE[dtype], None, "step %d seq %d lse" % (s, b))
