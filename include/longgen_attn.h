@@ -209,6 +209,25 @@ int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* 
                                 int sink, int window, int block, int stride, int cache_slots,
                                 int dtype, float scale, void* hip_stream);
 /*
+ * lg_sparse_attn_decode_cache for callers that cannot allocate or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the
+ * workspace), same kernels and bit-identical results; the partial results of the split over cache
+ * slots go to a scratch array of LG_DECODE_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (every GPU the library runs on holds it until the process ends).  Calls no allocating or
+ * freeing routine.  The first call on a device looks up the array's device address (make one call
+ * before capturing a graph).  LG_ERR_WORKSPACE when the call would need more scratch than the array
+ * holds (lg_sparse_attn_decode_cache_workspace_bytes tells; e.g. more than about 16000 (b, query head,
+ * split) records at D = 128): use lg_sparse_attn_decode_cache then.  All calls on one GPU share the
+ * array: two calls that may overlap in time (different streams) race; calls on one stream do not.
+ * Nothing in the array needs clearing between calls (every record is written before it is read).
+ */
+#define LG_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+int lg_sparse_attn_decode_cache_static(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                       float* lse, int B, int Hq, int Hkv, int N, int D,
+                                       int sink, int window, int block, int stride, int cache_slots,
+                                       int dtype, float scale, void* hip_stream);
+
+/*
  * Serving-style layout (the paper's inference section measures inside a paged-cache serving
  * engine): a paged cache shared by sequences of different lengths.
  *   k_pages, v_pages : [num_pages, Hkv, page_size, D] device; page_size a power of two, 16..4096

@@ -56,6 +56,8 @@ def lib():
         L.lg_sparse_attn_decode_cache_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode_cache.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 10 + [_i, _f, _vp]
         L.lg_sparse_attn_decode_cache.restype = _i
+        L.lg_sparse_attn_decode_cache_static.argtypes = [_vp] * 5 + [_i] * 10 + [_i, _f, _vp]
+        L.lg_sparse_attn_decode_cache_static.restype = _i
         L.lg_sparse_attn_decode_paged_workspace_bytes.argtypes = [_i] * 10
         L.lg_sparse_attn_decode_paged_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode_paged.argtypes = [_vp] * 7 + [_vp, _sz] + [_i] * 12 + [_i, _f, _vp]
@@ -239,6 +241,21 @@ def lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, workspace, N, sin
                                            scale, _stream(q))
     if st != 0:
         raise LgError(st, "lg_sparse_attn_decode_cache")
+
+
+def lg_sparse_attn_decode_cache_static(q, k_cache, v_cache, out, lse, N, sink, window, block=1, stride=0, scale=0.0):
+    """lg_sparse_attn_decode_cache without a workspace argument: the library's built-in scratch array is used."""
+    B, Hq, D = q.shape
+    Hkv, slots = k_cache.shape[1], k_cache.shape[2]
+    _check(q, B, Hq, D), _check(k_cache, B, Hkv, slots, D, like=q), _check(v_cache, B, Hkv, slots, D, like=q)
+    _check(out, B, Hq, D, like=q)
+    if lse is not None:
+        _check_lse(lse, B, Hq)
+    st = lib().lg_sparse_attn_decode_cache_static(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
+                                                  B, Hq, Hkv, N, D, sink, window, block, stride, slots,
+                                                  _dtype_code(q), scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_decode_cache_static")
 
 
 def decode_paged_workspace_bytes(B, Hq, Hkv, n_max, D, sink, window, block, stride, dtype):

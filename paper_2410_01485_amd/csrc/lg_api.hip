@@ -3,10 +3,34 @@
 // scheduler.  See include/longgen_attn.h for the contract of every entry point.
 #include <math.h>
 
+#include <mutex>
+
 #include "../../include/longgen_attn.h"
 #include "lg_kernels.h"
 
+// Scratch memory of the allocation-free decode call: one copy per GPU that loads the library, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// kernels receive the device address it returns, like any other workspace pointer.
+static __device__ __align__(256) unsigned char lg_static_scratch[LG_DECODE_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of lg_static_scratch on the current device (looked up once per device, under a lock),
+// or nullptr if the runtime refuses.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];
+void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(lg_static_scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -198,6 +222,25 @@ int lg_sparse_attn_decode_cache(const void* q, const void* k_cache, const void* 
   hipError_t e = lg_launch_decode(q, k_cache, v_cache, out, lse, workspace, B, Hq, Hkv, cache_slots, g, D,
                                   dtype, sh.scale, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LG_OK : LG_ERR_LAUNCH;
+}
+
+int lg_sparse_attn_decode_cache_static(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                       float* lse, int B, int Hq, int Hkv, int N, int D,
+                                       int sink, int window, int block, int stride, int cache_slots,
+                                       int dtype, float scale, void* hip_stream) {
+  if (!q || !k_cache || !v_cache || !out) return LG_ERR_NULL;
+  int st = check_decode(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  const size_t need = lg_sparse_attn_decode_cache_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);
+  if (need > (size_t)LG_DECODE_STATIC_SCRATCH_BYTES) return LG_ERR_WORKSPACE;  // beyond the built-in scratch
+  // run the remaining argument checks with a stand-in workspace before the first HIP call
+  st = lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, nullptr, 0, B, Hq, Hkv, N, D, sink, window, block,
+                                   stride, cache_slots, dtype, scale, hip_stream);
+  if (need == 0 || st != LG_ERR_WORKSPACE) return st;  // no scratch needed (done), or a bad argument
+  void* ws = static_scratch_ptr();
+  if (!ws) return LG_ERR_LAUNCH;
+  return lg_sparse_attn_decode_cache(q, k_cache, v_cache, out, lse, ws, LG_DECODE_STATIC_SCRATCH_BYTES, B, Hq, Hkv,
+                                     N, D, sink, window, block, stride, cache_slots, dtype, scale, hip_stream);
 }
 
 size_t lg_sparse_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int N, int D,
