@@ -59,7 +59,7 @@
  * the first HIP call, so they behave the same on a host without a GPU.
  *   LG_ERR_NULL         a required pointer is NULL (lse may be NULL in fwd and
  *                       decode: then it is not written)
- *   LG_ERR_INVALID_ARG  B,Hq,Hkv,N < 1; Hq % Hkv != 0; sink < 0; window < 1
+ *   LG_ERR_INVALID_ARG  B,Hq,Hkv,N < 1; N > 2^30; Hq % Hkv != 0; sink < 0; window < 1
  *                       (so every row has at least one live key); block < 0;
  *                       stride < 0; block > 1 with sink % block != 0 or
  *                       window % block != 0; a pointer not 16-byte aligned;
@@ -314,6 +314,20 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
  */
 int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int transposed, int row,
                        int32_t* order, size_t cap, size_t* count);
+
+/*
+ * Host-only: the per-lane register mask the bf16 kernels apply on a PARTIAL tile (a tile with live and
+ * dead pairs), computed in closed form from the pattern (Section 3.1) instead of evaluating the
+ * predicate per element.  Bit r (0..31) of *bits belongs to the entry at offset 4 * half + 8 * (r / 4) + r % 4
+ * along the tile (half = 0 or 1: the lane's half of the wave).
+ *   transposed == 0: the lane owns query row `fixed`; the tile is keys tile0 .. tile0 + 63
+ *                    (forward, dq): bit r = live(fixed, tile0 + offset)
+ *   transposed == 1: the lane owns key `fixed`; the tile is query rows tile0 .. tile0 + 63
+ *                    (dk/dv): bit r = (tile0 + offset < N) && live(tile0 + offset, fixed)
+ * fixed must be in [0, N), tile0 >= 0.  Runs the same source the kernels compile (no GPU needed).
+ */
+int lg_debug_partial_tile_bits(int N, int sink, int window, int block, int stride, int transposed,
+                               int fixed, int tile0, int half, uint32_t* bits);
 
 #ifdef __cplusplus
 }

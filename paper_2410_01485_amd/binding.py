@@ -72,6 +72,8 @@ def lib():
         L.lg_debug_decode_segments.restype = _i
         L.lg_debug_tile_walk.argtypes = [_i] * 7 + [_vp, _sz, ctypes.POINTER(_sz)]
         L.lg_debug_tile_walk.restype = _i
+        L.lg_debug_partial_tile_bits.argtypes = [_i] * 9 + [ctypes.POINTER(ctypes.c_uint32)]
+        L.lg_debug_partial_tile_bits.restype = _i
         L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
                                                    _vp, _vp, _sz, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
         L.lg_debug_tile_map.restype = _i
@@ -335,6 +337,16 @@ def lg_debug_tile_map(N, sink, window, block, stride, dtype, transposed):
     if st != 0:
         raise LgError(st, "lg_debug_tile_map")
     return tq.value, tk.value, row_ptr, col[:need.value], kind[:need.value]
+
+
+def lg_debug_partial_tile_bits(N, sink, window, block, stride, transposed, fixed, tile0, half):
+    """Host-only: the 32-bit register mask of a lane on a PARTIAL tile (see the header)."""
+    bits = ctypes.c_uint32(0)
+    st = lib().lg_debug_partial_tile_bits(N, sink, window, block, stride, transposed, fixed, tile0, half,
+                                          ctypes.byref(bits))
+    if st != 0:
+        raise LgError(st, "lg_debug_partial_tile_bits")
+    return int(bits.value)
 
 
 def lg_debug_tile_walk(N, sink, window, block, stride, transposed, row):

@@ -36,7 +36,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int check_common(int B, int Hq, int Hkv, int N, int D, int sink, int window, int block, int stride,
                  int dtype) {
-  if (B < 1 || Hq < 1 || Hkv < 1 || N < 1) return LG_ERR_INVALID_ARG;
+  if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || N > (1 << 30)) return LG_ERR_INVALID_ARG;
   if (Hq % Hkv != 0) return LG_ERR_INVALID_ARG;
   if (sink < 0 || window < 1 || block < 0 || stride < 0) return LG_ERR_INVALID_ARG;
   if (block > 1 && (sink % block != 0 || window % block != 0)) return LG_ERR_INVALID_ARG;
@@ -427,6 +427,18 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
   return LG_OK;
 }
 
+int lg_debug_partial_tile_bits(int N, int sink, int window, int block, int stride, int transposed,
+                               int fixed, int tile0, int half, uint32_t* bits) {
+  if (!bits) return LG_ERR_NULL;
+  int st = check_common(1, 1, 1, N, 64, sink, window, block, stride, LG_BF16);
+  if (st != LG_OK) return st;
+  if (fixed < 0 || fixed >= N || tile0 < 0 || tile0 > (1 << 30) || (half != 0 && half != 1))
+    return LG_ERR_INVALID_ARG;
+  const LgMask m = lg_make_mask(N, sink, window, block, stride);
+  *bits = transposed ? lg_row_bits(m, fixed, tile0, half) : lg_key_bits(m, fixed, tile0, half);
+  return LG_OK;
+}
+
 int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int transposed, int row,
                        int32_t* order, size_t cap, size_t* count) {
   if (!count) return LG_ERR_NULL;
@@ -444,7 +456,7 @@ int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int t
   if (!transposed) {
     const int q0 = row * Tq, q1 = (q0 + Tq - 1 < N - 1) ? q0 + Tq - 1 : N - 1;
     const LgQSched qs = lg_qsched_init(m, q0, q1);
-    if (m.b == 1 && m.stride == 0) {  // the token-granular kernels' rotated walk
+    if (m.stride == 0) {  // patterns without strided columns: the rotated walk
       const LgQWalk w = lg_qwalk_init(qs);
       for (int t = lg_qwalk_first(w); t >= 0; t = lg_qwalk_next(w, t)) emit(t);
     } else {

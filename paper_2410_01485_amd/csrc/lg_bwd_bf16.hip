@@ -145,10 +145,10 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
     dma.issue(vh + off, N - t * TK, lds0 + stage * STAGE + T::BYTES);
   };
 
-  // token-granular patterns walk the window run rotated (L2 sharing between neighbours)
+  // patterns without strided columns walk the window run rotated (L2 sharing between neighbours)
   const LgQWalk qw = lg_qwalk_init(qs);
   auto next_tile = [&](int prev) -> int {
-    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    if (TOKEN || m.stride == 0) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
     return lg_qsched_next(m, qs, prev);
   };
   int t = next_tile(-1);
@@ -177,12 +177,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
     const bool full = kind == LG_TILE_FULL;
     const int sk = stage * STAGE, sv = sk + T::BYTES;
     uint32_t bits = 0xffffffffu;
-    if (kind == LG_TILE_PARTIAL && !TOKEN) {
-      bits = 0;
-#pragma unroll 1
-      for (int r = 0; r < 32; ++r)
-        bits |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
-    }
+    if (kind == LG_TILE_PARTIAL && !TOKEN) bits = lg_key_bits(m, iq, k0, g);
     // Token mode: row i sees the keys [i - window + 1, i] and the sink keys below
     // min(sink, i + 1).  In tile coordinates (key = k0 + 4g + c, c a compile-time constant):
     const int hi = i - k0 - 4 * g;         // c <= hi           : causal
@@ -502,14 +497,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
     const int sq = VRES + buf * STAGE, sg = sq + OFF_G;
     const float* sL = reinterpret_cast<const float*>(smem + sq + OFF_L);
     uint32_t bits = ~0u;
-    if (!full && !TOKEN) {
-      bits = 0;
-#pragma unroll 1
-      for (int r = 0; r < 32; ++r) {
-        const int i = q0 + (r >> 4) * 32 + lg_crow(r & 15, g);
-        bits |= (uint32_t)(i < N && lg_live(m, i, j)) << r;
-      }
-    }
+    if (!full && !TOKEN) bits = lg_row_bits(m, j, q0, g);
     // Token mode: key j is seen by the rows [j, j + window - 1] (by every row >= j if it is a
     // sink key), below N.  In tile coordinates (row = q0 + 4g + c, c a compile-time constant):
     const int lo_c = j - q0 - 4 * g;                                   // c >= lo_c : causal
@@ -683,7 +671,11 @@ __device__ __forceinline__ void dkdv_wide_item(
   const int G = Hq / Hkv;
   const int N = m.N;
   const float sl2 = scale * LOG2E;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the thread index is made opaque per work item: what derives from it is recomputed for every item
+  // instead of being kept in registers, or spilled, across the resident kernel's loop over items)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   // work item: as in the kernel above
@@ -848,15 +840,7 @@ __device__ __forceinline__ void dkdv_wide_item(
         }
       } else {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          uint32_t w = 0;
-#pragma unroll 1
-          for (int r = 0; r < 32; ++r) {
-            const int i = q0 + (r >> 4) * 32 + lg_crow(r & 15, g);
-            w |= (uint32_t)(i < N && lg_live(m, i, j + 32 * kb)) << r;
-          }
-          bits[kb] = w;
-        }
+        for (int kb = 0; kb < 2; ++kb) bits[kb] = lg_row_bits(m, j + 32 * kb, q0, g);
       }
     }
     auto dead = [&](int kb, int qb, int r) -> bool { return !((bits[kb] >> (qb * 16 + r)) & 1); };
@@ -1164,7 +1148,7 @@ __device__ __forceinline__ void dq_wide_item(
   };
   const LgQWalk qw = lg_qwalk_init(qs);
   auto next_tile = [&](int prev) -> int {
-    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    if (TOKEN || m.stride == 0) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
     return lg_qsched_next(m, qs, prev);
   };
   // Tiles are handled in pairs: one barrier per two tiles (with one wave per SIMD nothing hides the
@@ -1207,8 +1191,7 @@ __device__ __forceinline__ void dq_wide_item(
           const int hi = i - k0 - 4 * g, lo = hi - (m.window - 1), se = m.sink - k0 - 4 * g;
           w = lg_reg_run(lo, hi + 1) | lg_reg_run(-1, min(se, hi + 1));
         } else {
-#pragma unroll 1
-          for (int r = 0; r < 32; ++r) w |= (uint32_t)lg_live(m, i, k0 + (r >> 4) * 32 + lg_crow(r & 15, g)) << r;
+          w = lg_key_bits(m, min(i, N - 1), k0, g);
         }
         bits[rb] = w;
       }

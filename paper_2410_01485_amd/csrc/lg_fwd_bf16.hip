@@ -113,10 +113,10 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
 
   // ring: tiles are issued up to 3 ahead of the one being computed
   const LgQSched qs = lg_qsched_init(m, q0, q1);
-  // token-granular patterns walk the window run rotated (L2 sharing between neighbours)
+  // patterns without strided columns walk the window run rotated (L2 sharing between neighbours)
   const LgQWalk qw = lg_qwalk_init(qs);
   auto next_tile = [&](int prev) -> int {
-    if (TOKEN) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
+    if (TOKEN || m.stride == 0) return prev < 0 ? lg_qwalk_first(qw) : lg_qwalk_next(qw, prev);
     return lg_qsched_next(m, qs, prev);
   };
   int t = next_tile(-1);  // tile to compute next
@@ -179,12 +179,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
           if (!live) sacc[kb][r] = -INFINITY;
         }
     } else if (!full) {
-      uint32_t bits = 0;
-#pragma unroll 1
-      for (int r = 0; r < 32; ++r) {
-        const int j = k0 + (r >> 4) * 32 + lg_crow(r & 15, g);
-        bits |= (uint32_t)lg_live(m, i, j) << r;
-      }
+      const uint32_t bits = lg_key_bits(m, min(i, N - 1), k0, g);  // a few runs of registers, in closed form
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll

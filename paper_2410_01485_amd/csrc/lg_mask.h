@@ -16,6 +16,8 @@
 #ifndef LG_MASK_H_
 #define LG_MASK_H_
 
+#include <stdint.h>
+
 #if defined(__HIPCC__)
 #include <hip/hip_runtime.h>
 #define LG_HD __host__ __device__ __forceinline__
@@ -231,6 +233,63 @@ LG_HD void lg_qtile_range(const LgMask& m, int k0, int k1, int Tq, int* lo, int*
     if (w < last) last = w;
   }
   *hi = (int)(last / Tq);
+}
+
+// ---------------------------------------------------------------------------------
+// Register masks of PARTIAL tiles (bf16 matrix-core kernels).  A lane of a wave holds, of a 64 x 32 (or
+// 32 x 64) block of pairs, ONE column and 32 of its entries in two stacked 32 x 32 accumulators: register
+// r = 0..31 of lane-half g is the entry at offset 4 g + c(r), c(r) = 8 (r / 4) + r % 4, along the other axis.
+// c grows with r, so the entries whose offset lies in [lo, hi) are a run of register bits, and every pattern
+// of the predicate decomposes into a few such runs: no per-element evaluation is needed.
+// lg_regs_below(x) = number of registers with c(r) < x.
+LG_HD int lg_regs_below(int x) {
+  x = x < 0 ? 0 : (x > 64 ? 64 : x);
+  const int rem = x & 7;
+  return 4 * (x >> 3) + (rem < 4 ? rem : 4);
+}
+LG_HD uint32_t lg_reg_run(int lo, int hi) {
+  const int a = lg_regs_below(lo), b = lg_regs_below(hi);
+  const uint32_t ma = a >= 32 ? ~0u : (1u << a) - 1u, mb = b >= 32 ? ~0u : (1u << b) - 1u;
+  return mb & ~ma;
+}
+LG_HD int lg_clamp_off(int x) { return x < -1 ? -1 : (x > 64 ? 64 : x); }
+
+// (All of the following is 32-bit arithmetic: the entry points accept sequences of up to 2^30 tokens.)
+// Forward / dq layout: the lane owns query row i, register r is key k0 + 4 g + c(r) of the 64-key tile at
+// k0.  Bit r of the result: live(i, that key).  The live keys of a row are its window run (keys from the
+// first key of block qb - wb + 1 up to i), the sink run (keys below `sink`), and the strided blocks.
+LG_HD uint32_t lg_key_bits(const LgMask& m, int i, int k0, int g) {
+  const int off = k0 + 4 * g;
+  const int hi = lg_clamp_off(i - off + 1);      // causal: offsets below hi
+  if (m.stride == 1) return lg_reg_run(-1, hi);  // every block is a strided column
+  const int jw = (lg_div_b(m, i) - m.wb + 1) * m.b;
+  uint32_t w = lg_reg_run(lg_clamp_off(jw - off), hi);
+  if (k0 < m.sink) {
+    const int se = lg_clamp_off(m.sink - off);
+    w |= lg_reg_run(-1, se < hi ? se : hi);
+  }
+  if (m.stride > 0) {
+    const int kb1 = lg_div_b(m, k0 + 63);
+    for (int kb = lg_next_strided_block(m, lg_div_b(m, k0)); kb <= kb1; kb += m.stride) {
+      const int s = kb * m.b - off;
+      const int e = lg_clamp_off(s + m.b);
+      w |= lg_reg_run(lg_clamp_off(s), e < hi ? e : hi);
+    }
+  }
+  return w;
+}
+
+// dk/dv layout: the lane owns key j, register r is query row q0 + 4 g + c(r) of the 64-row tile at q0.
+// Bit r: that row exists (below N) and live(row, j).  The rows that see a key are ONE run: from j to the
+// last row of block kb + wb - 1, or to the end of the sequence for a sink or strided-column key.
+LG_HD uint32_t lg_row_bits(const LgMask& m, int j, int q0, int g) {
+  const int off = q0 + 4 * g;
+  const int kb = lg_div_b(m, j);
+  const int nb = lg_div_b(m, m.N - 1) + 1;  // blocks of the sequence
+  const bool column = j < m.sink || (m.stride > 0 && lg_strided(m, kb));
+  const int qe = kb + m.wb;                 // first block whose rows no longer see the key through the window
+  const int end = (column || qe >= nb) ? m.N : qe * m.b;
+  return lg_reg_run(lg_clamp_off(j - off), lg_clamp_off(end - off));
 }
 
 // ---------------------------------------------------------------------------------

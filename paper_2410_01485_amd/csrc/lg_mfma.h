@@ -28,19 +28,6 @@ __device__ __forceinline__ f32x16_t lg_mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c
 // Row of register r (0..15) of a 32x32 accumulator for lane-half g.
 __device__ __forceinline__ constexpr int lg_crow(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
 
-// Two 32x32 accumulators stacked (registers r = 0..31, row offsets c(r) = 32 (r / 16) + lg_crow(r % 16, 0)
-// = 8 (r / 4) + r % 4): c grows with r, so the registers whose offset lies in [lo, hi) are a run
-// of bits.  lg_regs_below(x) = number of registers with c(r) < x.
-__device__ __forceinline__ int lg_regs_below(int x) {
-  x = min(max(x, 0), 64);
-  return 4 * (x >> 3) + min(x & 7, 4);
-}
-__device__ __forceinline__ uint32_t lg_reg_run(int lo, int hi) {
-  const int a = lg_regs_below(lo), b = lg_regs_below(hi);
-  const uint32_t ma = a >= 32 ? ~0u : (1u << a) - 1u, mb = b >= 32 ? ~0u : (1u << b) - 1u;
-  return mb & ~ma;
-}
-
 // Value held by lane ^ 32.
 __device__ __forceinline__ float lg_other_half(float x) {
   const unsigned u = __builtin_bit_cast(unsigned, x);

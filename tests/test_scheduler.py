@@ -111,3 +111,47 @@ def test_rotated_walks_align_neighbours():
     assert len(a) == len(b) == 69 and a[0] == 0 and b[0] == 0      # sink tile first, then the run of 68
     same = sum(int(x == y) for x, y in zip(a[1:], b[1:]))
     assert same == 64                                                # runs overlap in 64 of 68 tiles
+
+
+# ------------------------------------------------------------------ register masks of PARTIAL tiles
+def reg_offset(r, half):
+    return 4 * half + 8 * (r // 4) + r % 4
+
+
+BIT_CASES = [
+    (300, 16, 128, 1, 0), (1000, 64, 192, 64, 8), (1000, 48, 96, 48, 3), (900, 0, 16, 16, 1), (777, 3, 10, 1, 7),
+    (2000, 64, 1024, 64, 0), (1500, 32, 64, 32, 3), (600, 8, 24, 8, 5), (500, 4, 6, 2, 2), (640, 0, 192, 64, 64),
+    (257, 100, 3, 1, 2), (4100, 64, 1024, 64, 8), (333, 0, 1, 1, 0), (400, 10, 30, 10, 4),
+]
+
+
+@pytest.mark.parametrize("N,sink,window,block,stride", BIT_CASES)
+def test_partial_tile_register_masks_match_the_predicate(N, sink, window, block, stride):
+    """The closed-form per-lane masks of the bf16 kernels (runs of register bits) against the oracle's
+    predicate, bit for bit: every lane position of every 64-wide tile that can be PARTIAL, both orientations
+    (lane = query row over a key tile; lane = key over a query-row tile), both halves of the wave."""
+    mask = O.mask(N, sink, window, block, stride)
+    rng = np.random.default_rng(N + 7 * block + stride)
+    fixed_all = np.unique(np.concatenate([np.arange(min(N, 140)), rng.integers(0, N, 120), np.arange(max(0, N - 70), N)]))
+    for transposed in (0, 1):
+        for f in fixed_all:
+            f = int(f)
+            # tiles around the diagonal, the window edge, the sink, and a few others (ragged last tile included)
+            tiles = {0, 64, (f // 64) * 64, max(0, ((f - window) // 64) * 64), max(0, ((f + window) // 64) * 64),
+                     ((N - 1) // 64) * 64, int(rng.integers(0, N)) // 64 * 64, max(0, (f // 64) * 64 - 64)}
+            for t0 in sorted(tiles):
+                for half in (0, 1):
+                    got = lg.lg_debug_partial_tile_bits(N, sink, window, block, stride, transposed, f, t0, half)
+                    want = 0
+                    for r in range(32):
+                        x = t0 + reg_offset(r, half)
+                        if x < N and (mask[x, f] if transposed else mask[f, x]):
+                            want |= 1 << r
+                    assert got == want, (transposed, f, t0, half, bin(got), bin(want))
+
+
+def test_partial_tile_bits_argument_errors():
+    with pytest.raises(lg.LgError):
+        lg.lg_debug_partial_tile_bits(100, 0, 8, 1, 0, 0, 100, 0, 0)      # row outside the sequence
+    with pytest.raises(lg.LgError):
+        lg.lg_debug_partial_tile_bits(100, 0, 8, 1, 0, 0, 5, 0, 2)        # half is 0 or 1
