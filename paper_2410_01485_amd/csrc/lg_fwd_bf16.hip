@@ -156,10 +156,30 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    // The K rows are requested half a product ahead of the matrix instructions that use them (the compiler
+    // on its own asks for each operand just before its use, which leaves the LDS latency in the wave's
+    // critical path eight times per tile).
+    {
+      constexpr int HC = DC / 2;
+      bf16x8_t ka[2][HC], kn[2][HC];
 #pragma unroll
-    for (int dc = 0; dc < DC; ++dc)
+      for (int dc = 0; dc < HC; ++dc)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) sacc[kb] = lg_mfma32(rd.read_rows(smem, sk, kb, dc), qf[dc], sacc[kb]);
+        for (int kb = 0; kb < 2; ++kb) ka[kb][dc] = rd.read_rows(smem, sk, kb, dc);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int dc = 0; dc < HC; ++dc) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) kn[kb][dc] = rd.read_rows(smem, sk, kb, HC + dc);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) sacc[kb] = lg_mfma32(ka[kb][dc], qf[dc], sacc[kb]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int dc = 0; dc < HC; ++dc)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) sacc[kb] = lg_mfma32(kn[kb][dc], qf[HC + dc], sacc[kb]);
+    }
 
     // ---- online softmax (log2 domain) ----
     if (!full && TOKEN) {
