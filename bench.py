@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # scaled by what the same counter reads for a copy kernel of known size.  Counter runs are
 # separate from timed runs, so these are constants here, not measured by this script.
 MEASURED_HBM_BYTES = {
-    "fwd_bf16_kernel": (4.23e9, 1.090e9),
-    "dq_wide_bf16_kernel": (6.49e9, 1.110e9),
-    "dkdv_wide_bf16_kernel": (7.71e9, 2.160e9),
+    "fwd_bf16_kernel": (4.25e9, 1.090e9),
+    "dq_wide_bf16_kernel": (6.57e9, 1.110e9),
+    "dkdv_wide_bf16_kernel": (7.85e9, 2.160e9),
     "decode_kernel": (1.09e9, 0.000e9),
 }
 
