@@ -389,6 +389,11 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "Llama-2-7B-shaped training step of one sparse layer: causal sink+window "
                                "attention fwd+bwd, B1 H32/32 D128 N131072 bf16, sink 64, window 4096",
+                   "target": "50 % of the bf16 MFMA peak for prefill forward and backward, 70 % of the HBM peak "
+                             "for decode",
+                   "target_met": {"prefill_fwd": bool(fl_fwd / fwd_ms / 1e9 / PEAK_BF16_TFLOPS >= 0.5),
+                                  "prefill_bwd": bool(fl_bwd / bwd_ms / 1e9 / PEAK_BF16_TFLOPS >= 0.5),
+                                  "decode": bool(dec_gbs / PEAK_HBM_GBS >= 0.7)},
                    "live_pairs_per_head": pairs // (H * B), "flops_per_step": fl_fwd + fl_bwd,
                    "wall_ms_per_step": round(wall_ms, 3),
                    "ms_per_step_median": round(per_step[len(per_step) // 2], 3),
