@@ -43,6 +43,7 @@
  *                              exp(scaled scores) over the live keys of a row
  *     decode   q,out : [B, Hq, D]   k_cache,v_cache : [B, Hkv, sink+window, D]
  *              lse   : [B, Hq] float32
+ *     (the *_varlen calls pack sequences of different lengths per head: see there)
  * Element type of q/k/v/out/dout/dq/dk/dv/caches is `dtype` (lg_dtype);
  * accumulation and softmax are always float32.
  * GQA: query head hq reads kv head hq / (Hq/Hkv)  (consecutive query heads
@@ -150,6 +151,40 @@ int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const vo
                            int B, int Hq, int Hkv, int N, int D,
                            int sink, int window, int block, int stride,
                            int dtype, float scale, void* hip_stream, float* kernel_ms);
+
+/*
+ * Prefill over a batch of sequences of DIFFERENT lengths, packed without padding (Section 4.3 measures
+ * prefilling in a serving setting, where the requests of a batch differ in length; Section 3.2's
+ * kernel applied per sequence).  Layout: the sequences lie one after the other along the token axis
+ * of every head,
+ *     q,out,dout,dq : [Hq,  T, D]      k,v,dk,dv : [Hkv, T, D]      lse : [Hq, T] float32
+ * with T = cu_seqlens[num_seqs]; sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1 of each head.
+ * cu_seqlens is a HOST array of num_seqs + 1 non-decreasing offsets starting at 0, read during the
+ * call only.  Every sequence is attended on its own, positions counted from its first token:
+ * the results of sequence s equal lg_sparse_attn_fwd / lg_sparse_attn_bwd with B = 1 and
+ * N = its length on its rows (bit for bit on the paths those calls reproduce bit for bit).
+ * Empty sequences are allowed and skipped; when all are empty nothing is enqueued.
+ * One set of launches per sequence goes to hip_stream in order, each at the sequence's own
+ * length, so no work is spent on padding; the launches of short sequences (under ~64K query
+ * rows x heads) do not fill the GPU, which this entry point does not hide.
+ * The backward workspace is shared by the sequences (size = the largest any of them needs; the
+ * remarks on lg_sparse_attn_bwd's workspace apply).
+ * Errors, beyond the common ones: LG_ERR_NULL for cu_seqlens == NULL; LG_ERR_INVALID_ARG for
+ * num_seqs < 1, cu_seqlens[0] != 0, a decreasing offset, a sequence longer than 2^30, or
+ * Hq*T*D beyond 2^40 elements.  *_workspace_bytes returns 0 for invalid arguments.
+ */
+int lg_sparse_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
+                              const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                              int sink, int window, int block, int stride,
+                              int dtype, float scale, void* hip_stream);
+size_t lg_sparse_attn_bwd_varlen_workspace_bytes(const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                                                 int sink, int window, int block, int stride, int dtype);
+int lg_sparse_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                              const void* dout, void* dq, void* dk, void* dv,
+                              void* workspace, size_t workspace_bytes,
+                              const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                              int sink, int window, int block, int stride,
+                              int dtype, float scale, void* hip_stream);
 
 /*
  * Decode over the reduced KV cache (Section 3.2, second paragraph: loading the

@@ -44,6 +44,13 @@ def lib():
         L.lg_debug_bwd_kernel_ms.argtypes = [_vp] * 9 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp,
                                                                              ctypes.POINTER(_f)]
         L.lg_debug_bwd_kernel_ms.restype = _i
+        _ip = ctypes.POINTER(_i)
+        L.lg_sparse_attn_fwd_varlen.argtypes = [_vp] * 5 + [_ip] + [_i] * 8 + [_i, _f, _vp]
+        L.lg_sparse_attn_fwd_varlen.restype = _i
+        L.lg_sparse_attn_bwd_varlen_workspace_bytes.argtypes = [_ip] + [_i] * 9
+        L.lg_sparse_attn_bwd_varlen_workspace_bytes.restype = _sz
+        L.lg_sparse_attn_bwd_varlen.argtypes = [_vp] * 9 + [_vp, _sz] + [_ip] + [_i] * 8 + [_i, _f, _vp]
+        L.lg_sparse_attn_bwd_varlen.restype = _i
         L.lg_sparse_attn_decode_workspace_bytes.argtypes = [_i] * 8
         L.lg_sparse_attn_decode_workspace_bytes.restype = _sz
         L.lg_sparse_attn_decode.argtypes = [_vp] * 5 + [_vp, _sz] + [_i] * 9 + [_i, _f, _vp]
@@ -181,6 +188,58 @@ def lg_debug_bwd_kernel_ms(q, k, v, out, lse, dout, dq, dk, dv, workspace, sink,
     if st != 0:
         raise LgError(st, "lg_debug_bwd_kernel_ms")
     return [float(x) for x in ms]
+
+
+def _cu_array(cu_seqlens):
+    """The host array of offsets the *_varlen calls take: (ctypes int array, number of sequences)."""
+    cu = [int(x) for x in cu_seqlens]
+    if len(cu) < 2:
+        raise ValueError("cu_seqlens needs at least two entries (one sequence)")
+    return (_i * len(cu))(*cu), len(cu) - 1
+
+
+def lg_sparse_attn_fwd_varlen(q, k, v, out, lse, cu_seqlens, sink, window, block=1, stride=0, scale=0.0):
+    """Forward over packed sequences: q,out [Hq,T,D], k,v [Hkv,T,D], lse [Hq,T] or None; cu_seqlens is a host
+    sequence of num_seqs + 1 offsets (0 first, T last)."""
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    cu, ns = _cu_array(cu_seqlens)
+    if cu[ns] != T:
+        raise ValueError("cu_seqlens ends at %d, the tensors hold %d tokens" % (cu[ns], T))
+    _check(q, Hq, T, D), _check(k, Hkv, T, D, like=q), _check(v, Hkv, T, D, like=q), _check(out, Hq, T, D, like=q)
+    if lse is not None:
+        _check_lse(lse, Hq, T)
+    st = lib().lg_sparse_attn_fwd_varlen(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), cu, ns, Hq, Hkv, D,
+                                         sink, window, block, stride, _dtype_code(q), scale, _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_fwd_varlen")
+
+
+def bwd_varlen_workspace_bytes(cu_seqlens, Hq, Hkv, D, sink, window, block, stride, dtype):
+    cu, ns = _cu_array(cu_seqlens)
+    return int(lib().lg_sparse_attn_bwd_varlen_workspace_bytes(cu, ns, Hq, Hkv, D, sink, window, block, stride,
+                                                               dtype))
+
+
+def lg_sparse_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, workspace, cu_seqlens, sink, window, block=1,
+                              stride=0, scale=0.0):
+    """dq, dk, dv <- backward of lg_sparse_attn_fwd_varlen (same packed layout)."""
+    Hq, T, D = q.shape
+    Hkv = k.shape[0]
+    cu, ns = _cu_array(cu_seqlens)
+    if cu[ns] != T:
+        raise ValueError("cu_seqlens ends at %d, the tensors hold %d tokens" % (cu[ns], T))
+    for t in (q, out, dout, dq):
+        _check(t, Hq, T, D, like=q)
+    for t in (k, v, dk, dv):
+        _check(t, Hkv, T, D, like=q)
+    _check_lse(lse, Hq, T)
+    st = lib().lg_sparse_attn_bwd_varlen(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                         _ptr(dk), _ptr(dv), _ptr(workspace), _ws_bytes(workspace), cu, ns,
+                                         Hq, Hkv, D, sink, window, block, stride, _dtype_code(q), scale,
+                                         _stream(q))
+    if st != 0:
+        raise LgError(st, "lg_sparse_attn_bwd_varlen")
 
 
 def decode_workspace_bytes(B, Hq, Hkv, N, D, sink, window, dtype):

@@ -159,6 +159,114 @@ int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const vo
                   window, block, stride, dtype, scale, hip_stream, kernel_ms);
 }
 
+// Packed sequences of different lengths: validates cu_seqlens (host; num_seqs + 1 non-decreasing offsets
+// from 0) and the common arguments for the longest sequence; *total = cu_seqlens[num_seqs], *longest =
+// the longest sequence (0 when every sequence is empty).
+static int check_varlen(const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D, int sink, int window,
+                        int block, int stride, int dtype, int* total, int* longest) {
+  if (!cu_seqlens) return LG_ERR_NULL;
+  if (num_seqs < 1 || cu_seqlens[0] != 0) return LG_ERR_INVALID_ARG;
+  int mx = 0;
+  for (int x = 0; x < num_seqs; ++x) {
+    if (cu_seqlens[x + 1] < cu_seqlens[x]) return LG_ERR_INVALID_ARG;
+    const int n = cu_seqlens[x + 1] - cu_seqlens[x];
+    mx = n > mx ? n : mx;
+  }
+  *total = cu_seqlens[num_seqs];
+  *longest = mx;
+  int st = check_common(1, Hq, Hkv, mx > 0 ? mx : 1, D, sink, window, block, stride, dtype);
+  if (st != LG_OK) return st;
+  return (double)Hq * (double)*total * (double)D > 1099511627776.0 ? LG_ERR_INVALID_ARG : LG_OK;
+}
+
+int lg_sparse_attn_fwd_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
+                              const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                              int sink, int window, int block, int stride,
+                              int dtype, float scale, void* hip_stream) {
+  if (!q || !k || !v || !out) return LG_ERR_NULL;
+  int T = 0, longest = 0;
+  int st = check_varlen(cu_seqlens, num_seqs, Hq, Hkv, D, sink, window, block, stride, dtype, &T, &longest);
+  if (st != LG_OK) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+    return LG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t es = dtype == LG_F32 ? 4 : 2;
+  for (int x = 0; x < num_seqs; ++x) {
+    const int n = cu_seqlens[x + 1] - cu_seqlens[x];
+    if (n == 0) continue;
+    const LgShape sh = make_shape(1, Hq, Hkv, n, D, scale);
+    LgMask m = lg_make_mask(n, sink, window, block, stride);
+    m.ld = T;  // a head's rows of all sequences lie side by side
+    const size_t off = (size_t)cu_seqlens[x] * D * es;
+    const char* qs = (const char*)q + off;
+    const char* ks = (const char*)k + off;
+    const char* vs = (const char*)v + off;
+    char* os = (char*)out + off;
+    float* ls = lse ? lse + cu_seqlens[x] : nullptr;
+    const hipError_t e = (dtype == LG_F32)
+        ? lg_launch_fwd_f32((const float*)qs, (const float*)ks, (const float*)vs, (float*)os, ls, sh, m, s)
+        : lg_launch_fwd_bf16(qs, ks, vs, os, ls, sh, m, s);
+    if (e != hipSuccess) return LG_ERR_LAUNCH;
+  }
+  return LG_OK;
+}
+
+size_t lg_sparse_attn_bwd_varlen_workspace_bytes(const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                                                 int sink, int window, int block, int stride, int dtype) {
+  int T = 0, longest = 0;
+  if (check_varlen(cu_seqlens, num_seqs, Hq, Hkv, D, sink, window, block, stride, dtype, &T, &longest) != LG_OK)
+    return 0;
+  size_t need = 256;  // never 0 for valid arguments: 0 is the error value
+  for (int x = 0; x < num_seqs; ++x) {
+    const int n = cu_seqlens[x + 1] - cu_seqlens[x];
+    if (n == 0) continue;
+    const size_t b = lg_bwd_workspace_bytes(make_shape(1, Hq, Hkv, n, D, 0.0f),
+                                            lg_make_mask(n, sink, window, block, stride), dtype);
+    need = b > need ? b : need;
+  }
+  return need;
+}
+
+int lg_sparse_attn_bwd_varlen(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                              const void* dout, void* dq, void* dk, void* dv,
+                              void* workspace, size_t workspace_bytes,
+                              const int* cu_seqlens, int num_seqs, int Hq, int Hkv, int D,
+                              int sink, int window, int block, int stride,
+                              int dtype, float scale, void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return LG_ERR_NULL;
+  int T = 0, longest = 0;
+  int st = check_varlen(cu_seqlens, num_seqs, Hq, Hkv, D, sink, window, block, stride, dtype, &T, &longest);
+  if (st != LG_OK) return st;
+  const void* ptrs[] = {q, k, v, out, lse, dout, dq, dk, dv, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LG_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < lg_sparse_attn_bwd_varlen_workspace_bytes(
+                                          cu_seqlens, num_seqs, Hq, Hkv, D, sink, window, block, stride, dtype))
+    return LG_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t es = dtype == LG_F32 ? 4 : 2;
+  for (int x = 0; x < num_seqs; ++x) {
+    const int n = cu_seqlens[x + 1] - cu_seqlens[x];
+    if (n == 0) continue;
+    const LgShape sh = make_shape(1, Hq, Hkv, n, D, scale);
+    LgMask m = lg_make_mask(n, sink, window, block, stride);
+    m.ld = T;
+    const size_t off = (size_t)cu_seqlens[x] * D * es;
+    const char *qs = (const char*)q + off, *ks = (const char*)k + off, *vs = (const char*)v + off;
+    const char *os = (const char*)out + off, *gs = (const char*)dout + off;
+    char *dqs = (char*)dq + off, *dks = (char*)dk + off, *dvs = (char*)dv + off;
+    const float* ls = lse + cu_seqlens[x];
+    // the launches of one sequence follow those of the one before on the stream, so all of them
+    // use the same workspace, each with the layout of its own length
+    const hipError_t e = (dtype == LG_F32)
+        ? lg_launch_bwd_f32((const float*)qs, (const float*)ks, (const float*)vs, (const float*)os, ls,
+                            (const float*)gs, (float*)dqs, (float*)dks, (float*)dvs, workspace, sh, m, s, nullptr)
+        : lg_launch_bwd_bf16(qs, ks, vs, os, ls, gs, dqs, dks, dvs, workspace, sh, m, s, nullptr);
+    if (e != hipSuccess) return LG_ERR_LAUNCH;
+  }
+  return LG_OK;
+}
+
 static int check_decode(int B, int Hq, int Hkv, int N, int D, int sink, int window, int block,
                         int stride, int dtype) {
   int st = check_common(B, Hq, Hkv, N, D, sink, window, block, stride, dtype);

@@ -96,9 +96,9 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int q0 = qt * TQ, q1 = min(q0 + TQ - 1, N - 1);
-  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
-  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * m.ld) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * m.ld) * D;
   const int i = q0 + wave * 32 + n;
   const int iq = min(i, N - 1);
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(512) void dq_bf16_kernel(
   }
   di += lg_other_half(di);  // Delta of row i
   const float sl2 = scale * LOG2E;
-  const float lse_i = lse[(size_t)(b * Hq + hq) * N + iq];
+  const float lse_i = lse[(size_t)(b * Hq + hq) * m.ld + iq];
   float lse2 = lse_i * LOG2E;
   if (g == 0 && i < N) {
     ndelta[(size_t)(b * Hq + hq) * N + i] = -di;
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
   }
   const int b = bh / Hkv, hk = bh % Hkv;
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t kbase = ((size_t)(b * Hkv + hk) * m.ld) * D;
   // this wave's 32 keys: part of the key tile, or half of one of the virtual tile's column groups
   int kw0 = k0 + wave_s * 32;
   int col_gi = 0;        // COLUMN: index of this wave's column group
@@ -460,8 +460,9 @@ __global__ __launch_bounds__(512) void dkdv_bf16_kernel(
       const float* src = (wave == 0 ? nlse : ndelta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
-    dma.issue(q + (row0 + q0) * D, N - q0, st);
-    dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
+    const size_t urow0 = (size_t)(b * Hq + hq) * m.ld;  // the head's first row in the caller's tensors
+    dma.issue(q + (urow0 + q0) * D, N - q0, st);
+    dma.issue(dout + (urow0 + q0) * D, N - q0, st + OFF_G);
   };
 
   // The query tiles [lo, hi] of a head are walked rotated: at step x the tile congruent to x
@@ -712,7 +713,7 @@ __device__ __forceinline__ void dkdv_wide_item(
   }
   const int b = bh / Hkv, hk = bh % Hkv;
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t kbase = ((size_t)(b * Hkv + hk) * m.ld) * D;
   // this wave's 64 keys: a quarter of the key tile, or one column group of the virtual tile;
   // lane n holds keys kw0 + n and kw0 + 32 + n
   int kw0 = k0 + wave_s * 64;
@@ -794,8 +795,9 @@ __device__ __forceinline__ void dkdv_wide_item(
       const float* src = (wave == 0 ? nlse : ndelta) + row0 + min(q0 + lane, N - 1);
       lg_dma_f32x64(src, st + OFF_L + wave * 256);
     }
-    dma.issue(q + (row0 + q0) * D, N - q0, st);
-    dma.issue(dout + (row0 + q0) * D, N - q0, st + OFF_G);
+    const size_t urow0 = (size_t)(b * Hq + hq) * m.ld;  // the head's first row in the caller's tensors
+    dma.issue(q + (urow0 + q0) * D, N - q0, st);
+    dma.issue(dout + (urow0 + q0) * D, N - q0, st + OFF_G);
   };
 
   const int u0 = lo + (per_head - lo % per_head) % per_head;  // rotated walk, as above
@@ -1090,9 +1092,9 @@ __device__ __forceinline__ void dq_wide_item(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int q0 = qt * TQ, q1 = min(q0 + TQ - 1, N - 1);
-  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
-  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * m.ld) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * m.ld) * D;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int qw0 = min(q0 + wave_s * 64, N - 1), qw1 = min(q0 + wave_s * 64 + 63, N - 1);  // this wave's rows
   const int i0 = q0 + wave * 64 + n;  // this lane's row of row block 0 (block 1: + 32)
@@ -1112,7 +1114,7 @@ __device__ __forceinline__ void dq_wide_item(
       di = lg_dot8(gw, *reinterpret_cast<const uint4*>(out + qbase + (size_t)iq * D + dc * 16 + g * 8), di);
     }
     di += lg_other_half(di);  // Delta of the row
-    lse_i[rb] = lse[(size_t)(b * Hq + hq) * N + iq];
+    lse_i[rb] = lse[(size_t)(b * Hq + hq) * m.ld + iq];
     lse2[rb] = lse_i[rb] * LOG2E;
 #pragma unroll
     for (int r = 0; r < 16; ++r) ndl[rb][r] = -di;

@@ -41,23 +41,25 @@ __device__ __forceinline__ float dot16(const __hip_bfloat16* a, const __hip_bflo
 }
 
 // One row per LPR = D*sizeof(T)/16 lanes; rows = B*Hq*N.  delta = dsign * <dout, out>;
-// lse2 (optional) = lse * lscale.
+// lse2 (optional) = lse * lscale.  delta and lse2 are dense [B*Hq, N]; in dout, out and lse one head
+// follows the other after ld rows.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ dout, const T* __restrict__ out,
                                                     float* __restrict__ delta, const float* __restrict__ lse,
                                                     float* __restrict__ lse2, float dsign, float lscale,
-                                                    long long rows) {
+                                                    long long rows, int N, int ld) {
   constexpr int E = 16 / sizeof(T);
   constexpr int LPR = D / E;
   const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
   const int c = threadIdx.x % LPR;
-  const long long rr = row < rows ? row : rows - 1;
+  long long rr = row < rows ? row : rows - 1;
+  if (ld != N) rr = (rr / N) * ld + rr % N;
   float s = dot16(dout + rr * D + c * E, out + rr * D + c * E);
 #pragma unroll
   for (int x = 1; x < LPR; x <<= 1) s += __shfl_xor(s, x);
   if (c == 0 && row < rows) {
     delta[row] = dsign * s;
-    if (lse2) lse2[row] = lse[row] * lscale;
+    if (lse2) lse2[row] = lse[rr] * lscale;
   }
 }
 
@@ -77,9 +79,10 @@ __global__ __launch_bounds__(256) void dq_f32_kernel(const float* __restrict__ q
   const int hk = hq / (Hq / Hkv);
   const int q0 = qt * TQ, q1 = min(q0 + TQ - 1, N - 1);
   const int i = q0 + r, iq = min(i, N - 1);
-  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
-  const size_t rbase = (size_t)(b * Hq + hq) * N;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+  const size_t kbase = ((size_t)(b * Hkv + hk) * m.ld) * D;
+  const size_t rbase = (size_t)(b * Hq + hq) * N;     // Delta (workspace, dense)
+  const size_t lbase = (size_t)(b * Hq + hq) * m.ld;  // lse (caller's)
 
   float qr[DS], gr[DS], acc[DS];
 #pragma unroll
@@ -88,7 +91,7 @@ __global__ __launch_bounds__(256) void dq_f32_kernel(const float* __restrict__ q
     gr[d] = dout[qbase + (size_t)iq * D + c * DS + d];
     acc[d] = 0.f;
   }
-  const float li = lse[rbase + iq], di = delta[rbase + iq];
+  const float li = lse[lbase + iq], di = delta[rbase + iq];
 
   const LgQSched qs = lg_qsched_init(m, q0, q1);
   for (int t = lg_qsched_next(m, qs, -1); t >= 0; t = lg_qsched_next(m, qs, t)) {
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const float* __restrict__
   const int G = Hq / Hkv;
   const int k0 = kt * TK, k1 = min(k0 + TK - 1, N - 1);
   const int j = k0 + r, jk = min(j, N - 1);
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t kbase = ((size_t)(b * Hkv + hk) * m.ld) * D;
 
   float kr[DS], vr[DS], ak[DS], av[DS];
 #pragma unroll
@@ -163,8 +166,9 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const float* __restrict__
 
   for (int gq = 0; gq < G; ++gq) {
     const int hq = hk * G + gq;
-    const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-    const size_t rbase = (size_t)(b * Hq + hq) * N;
+    const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+    const size_t rbase = (size_t)(b * Hq + hq) * N;     // Delta (workspace, dense)
+    const size_t lbase = (size_t)(b * Hq + hq) * m.ld;  // lse (caller's)
     for (int u = lo; u <= hi; ++u) {
       const int q0 = u * TQ, q1 = min(q0 + TQ - 1, N - 1);
       const bool full = lg_tile_kind(m, q0, q1, k0, k0 + TK - 1) == LG_TILE_FULL && q0 + TQ <= N;
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const float* __restrict__
       }
       if (tid < TQ) {
         const int i = min(q0 + tid, N - 1);
-        sL[tid] = lse[rbase + i];
+        sL[tid] = lse[lbase + i];
         sD[tid] = delta[rbase + i];
       }
       __syncthreads();
@@ -219,14 +223,14 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const float* __restrict__
 
 template <typename T>
 hipError_t launch_delta_t(const void* dout, const void* out, float* delta, const float* lse, float* lse2,
-                          float dsign, float lscale, long long rows, int D, hipStream_t s) {
+                          float dsign, float lscale, long long rows, int N, int ld, int D, hipStream_t s) {
   const int lpr = D * (int)sizeof(T) / 16;
   const int rpb = 256 / lpr;
   const unsigned grid = (unsigned)((rows + rpb - 1) / rpb);
   if (D == 64)
-    delta_kernel<T, 64><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows);
+    delta_kernel<T, 64><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows, N, ld);
   else
-    delta_kernel<T, 128><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows);
+    delta_kernel<T, 128><<<grid, 256, 0, s>>>((const T*)dout, (const T*)out, delta, lse, lse2, dsign, lscale, rows, N, ld);
   return hipGetLastError();
 }
 
@@ -234,9 +238,11 @@ hipError_t launch_delta_t(const void* dout, const void* out, float* delta, const
 
 // Delta pre-pass for either dtype (used by both backward paths).
 hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, const float* lse, float* lse2,
-                           float dsign, float lscale, long long rows, int D, int dtype, hipStream_t s) {
-  return dtype == LG_F32 ? launch_delta_t<float>(dout, out, delta, lse, lse2, dsign, lscale, rows, D, s)
-                         : launch_delta_t<__hip_bfloat16>(dout, out, delta, lse, lse2, dsign, lscale, rows, D, s);
+                           float dsign, float lscale, long long rows, int N, int ld, int D, int dtype,
+                           hipStream_t s) {
+  return dtype == LG_F32
+             ? launch_delta_t<float>(dout, out, delta, lse, lse2, dsign, lscale, rows, N, ld, D, s)
+             : launch_delta_t<__hip_bfloat16>(dout, out, delta, lse, lse2, dsign, lscale, rows, N, ld, D, s);
 }
 
 size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype) {
@@ -252,7 +258,8 @@ hipError_t lg_launch_bwd_f32(const float* q, const float* k, const float* v, con
                              hipEvent_t* ev) {
   float* delta = (float*)ws;
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipError_t e = lg_launch_delta(dout, out, delta, nullptr, nullptr, 1.f, 0.f, (long long)sh.B * sh.Hq * sh.N, sh.D, LG_F32, s);
+  hipError_t e = lg_launch_delta(dout, out, delta, nullptr, nullptr, 1.f, 0.f, (long long)sh.B * sh.Hq * sh.N, sh.N, m.ld, sh.D,
+                                 LG_F32, s);
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 gq((sh.N + LG_F32_TQ - 1) / LG_F32_TQ, sh.Hq, sh.B);

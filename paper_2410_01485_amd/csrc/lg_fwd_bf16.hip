@@ -71,9 +71,9 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
   const int n = lane & 31, g = lane >> 5;
   const int q0 = qt * TQ;
   const int q1 = min(q0 + TQ - 1, N - 1);
-  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * N) * D;
-  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * m.ld) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * m.ld) * D;
   const int i = q0 + wave * 32 + n;  // this lane's query row
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int qw0 = min(q0 + wave_s * 32, N - 1), qw1 = min(q0 + wave_s * 32 + 31, N - 1);  // this wave's rows
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
         *reinterpret_cast<uint2*>(orow + db * 32 + 8 * r4) = w;
       }
     if (lse != nullptr && g == 0)
-      lse[(size_t)(b * Hq + hq) * N + i] = (mref * scale_log2e + log2f(l)) * 0.69314718055994530942f;
+      lse[(size_t)(b * Hq + hq) * m.ld + i] = (mref * scale_log2e + log2f(l)) * 0.69314718055994530942f;
   }
 }
 

@@ -32,8 +32,8 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
   const int q1 = min(q0 + TQ - 1, N - 1);
   const int i = q0 + r;             // this lane's query row
   const int iq = min(i, N - 1);     // clamped for loads
-  const size_t qbase = ((size_t)(b * Hq + hq) * N) * D;
-  const size_t kbase = ((size_t)(b * Hkv + hk) * N) * D;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
+  const size_t kbase = ((size_t)(b * Hkv + hk) * m.ld) * D;
 
   float qr[DS], o[DS];
 #pragma unroll
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
     const float inv = 1.f / lrow;
 #pragma unroll
     for (int d = 0; d < DS; ++d) out[qbase + (size_t)i * D + c * DS + d] = o[d] * inv;
-    if (lse != nullptr && c == 0) lse[(size_t)(b * Hq + hq) * N + i] = mrow + logf(lrow);
+    if (lse != nullptr && c == 0) lse[(size_t)(b * Hq + hq) * m.ld + i] = mrow + logf(lrow);
   }
 }
 

@@ -31,9 +31,11 @@ hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void*
                               const LgShape& sh, const LgMask& m, hipStream_t s);
 
 // delta_i = dsign * <dout_i, out_i> for rows = B*Hq*N rows of D elements of either dtype;
-// lse2 (may be NULL) = lse * lscale.
+// lse2 (may be NULL) = lse * lscale.  delta and lse2 are dense; in dout, out and lse a head's N rows are
+// followed by the next head's after ld rows.
 hipError_t lg_launch_delta(const void* dout, const void* out, float* delta, const float* lse, float* lse2,
-                           float dsign, float lscale, long long rows, int D, int dtype, hipStream_t s);
+                           float dsign, float lscale, long long rows, int N, int ld, int D, int dtype,
+                           hipStream_t s);
 size_t lg_bwd_workspace_bytes(const LgShape& sh, const LgMask& m, int dtype);
 size_t lg_bwd_bf16_workspace_bytes(const LgShape& sh, const LgMask& m, size_t head_bytes);
 // ev: NULL, or 4 events recorded before the Delta pre-pass, between the kernels and after the

@@ -27,6 +27,8 @@
 
 struct LgMask {
   int N;       // sequence length (queries = keys)
+  int ld;      // rows from one head to the next in the caller's tensors: N in the batch layout, the
+               // total number of tokens when sequences of different lengths are packed per head
   int sink;    // tokens
   int window;  // tokens
   int b;       // max(block, 1): pattern granularity in tokens
@@ -46,6 +48,7 @@ LG_HD int lg_log2_exact(int x) {
 LG_HD LgMask lg_make_mask(int N, int sink, int window, int block, int stride) {
   LgMask m;
   m.N = N;
+  m.ld = N;
   m.b = block > 1 ? block : 1;
   // Values beyond the sequence change nothing; clamping them keeps every product
   // below in int range.
@@ -326,6 +329,7 @@ LG_HD void lg_decsegs_push(LgDecSegs& g, int start, int len) {
 LG_HD LgMask lg_make_cache_mask(int N, int sink, int window, int block, int stride) {
   LgMask m;
   m.N = N;
+  m.ld = N;
   m.b = block > 1 ? block : 1;
   m.sb = sink / m.b;
   m.wb = window / m.b;

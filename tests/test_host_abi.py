@@ -68,6 +68,42 @@ def test_bwd_argument_errors():
     assert lg.bwd_workspace_bytes(1, 3, 2, 64, 64, 4, 8, 1, 0, lg.LG_BF16) == 0   # invalid -> 0
 
 
+def test_varlen_argument_errors_and_workspace():
+    """The packed, different-lengths calls validate the offsets and everything else before the first HIP call;
+    a pack of empty sequences enqueues nothing and succeeds; the workspace is the largest any sequence needs."""
+    L = lg.lib()
+
+    def cu_arr(cu):
+        return None if cu is None else (ctypes.c_int * len(cu))(*cu)
+
+    def fwd_v(cu=(0, 100, 300), ns=None, q=P, lse=P, Hq=4, Hkv=2, D=128, window=8, block=1, sink=4, dtype=lg.LG_BF16):
+        ns = (len(cu) - 1 if cu is not None else 1) if ns is None else ns
+        return L.lg_sparse_attn_fwd_varlen(q, P, P, P, lse, cu_arr(cu), ns, Hq, Hkv, D, sink, window, block, 0,
+                                           dtype, 0.0, None)
+
+    def bwd_v(cu=(0, 100, 300), ws=P, ws_bytes=1 << 30, lse=P, dq=P, D=128):
+        return L.lg_sparse_attn_bwd_varlen(P, P, P, P, lse, P, dq, P, P, ws, ws_bytes, cu_arr(cu), len(cu) - 1, 4, 2,
+                                           D, 4, 8, 1, 0, lg.LG_BF16, 0.0, None)
+
+    assert fwd_v(cu=None) == 1 and fwd_v(q=None) == 1
+    assert fwd_v(ns=0) == 2 and fwd_v(cu=(1, 100)) == 2 and fwd_v(cu=(0, 100, 99)) == 2
+    assert fwd_v(Hq=3) == 2 and fwd_v(window=0) == 2 and fwd_v(block=8, sink=4) == 2 and fwd_v(q=P + 4) == 2
+    assert fwd_v(D=32) == 3 and fwd_v(dtype=7) == 3
+    assert fwd_v(cu=(0, (1 << 30) + 1)) == 2                       # a sequence beyond 2^30 tokens
+    assert fwd_v(cu=(0, 1 << 30, (1 << 31) - 1), Hq=32, Hkv=32) == 2   # Hq * T * D beyond 2^40 elements
+    assert fwd_v(cu=(0, 0, 0, 0)) == 0 and fwd_v(cu=(0, 0), lse=None) == 0   # nothing to do: no HIP call made
+    assert bwd_v(lse=None) == 1 and bwd_v(dq=P + 8) == 2 and bwd_v(D=48) == 3
+    assert bwd_v(cu=(0, 5, 3)) == 2 and bwd_v(cu=(0, 0)) == 0
+    need = lg.bwd_varlen_workspace_bytes([0, 100, 300, 300, 350], 4, 2, 128, 4, 8, 1, 0, lg.LG_BF16)
+    assert need == max(lg.bwd_workspace_bytes(1, 4, 2, n, 128, 4, 8, 1, 0, lg.LG_BF16) for n in (100, 200, 50))
+    assert bwd_v(ws_bytes=need - 1, cu=(0, 100, 300, 300, 350)) == 4 and bwd_v(ws=None, cu=(0, 100, 300)) == 4
+    assert lg.bwd_varlen_workspace_bytes([0, 0], 4, 2, 128, 4, 8, 1, 0, lg.LG_BF16) == 256
+    assert lg.bwd_varlen_workspace_bytes([0, 5, 3], 4, 2, 128, 4, 8, 1, 0, lg.LG_BF16) == 0
+    assert lg.bwd_varlen_workspace_bytes([0, 5], 4, 2, 48, 4, 8, 1, 0, lg.LG_BF16) == 0
+    with pytest.raises(ValueError):
+        lg.bwd_varlen_workspace_bytes([0], 4, 2, 128, 4, 8, 1, 0, lg.LG_BF16)
+
+
 def test_decode_argument_errors():
     L = lg.lib()
 

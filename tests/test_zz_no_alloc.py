@@ -50,6 +50,40 @@ def test_static_scratch_decode_two_calls_second_smaller(dtype):
     one_call(2, 8, 2, 6000, 128, 64, 4096, 1, 0, dtype, 303)
 
 
+@pytest.mark.gpu
+def test_static_scratch_decode_replays_from_a_graph():
+    """The caller the entry point exists for: a decode step captured into a HIP graph (no allocation, no
+    clearing node, no synchronisation inside the capture).  The scratch address is looked up at the first
+    call on the device, which therefore happens before the capture.  Every replay runs on fresh inputs, with
+    eager work between replays, and is compared with the eager workspace call."""
+    B, Hq, Hkv, N, D, sink, window, block, stride = 2, 8, 2, 6000, 128, 64, 4096, 1, 0
+    dt = torch.bfloat16
+    slots = lg.lg_kv_cache_slots(N, sink, window, block, stride)
+    kc = torch.zeros(B, Hkv, slots, D, dtype=dt, device=DEV)
+    vc = torch.zeros_like(kc)
+    q1 = torch.zeros(B, Hq, D, dtype=dt, device=DEV)
+    out = torch.empty_like(q1)
+    lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+    ws = torch.empty(lg.decode_cache_workspace_bytes(B, Hq, Hkv, N, D, sink, window, block, stride, lg.LG_BF16),
+                     dtype=torch.uint8, device=DEV)
+    ref_out, ref_lse = torch.empty_like(out), torch.empty_like(lse)
+    lg.lg_sparse_attn_decode_cache_static(q1, kc, vc, out, lse, N, sink, window, block, stride)   # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lg.lg_sparse_attn_decode_cache_static(q1, kc, vc, out, lse, N, sink, window, block, stride)
+    for rep in range(3):
+        q, k, v = lg_synth.prefill_inputs(B, Hq, Hkv, N, D, 310 + rep, dt)
+        lg.lg_kv_ring_append(k.to(DEV), v.to(DEV), kc, vc, 0, sink, window, block, stride)
+        q1.copy_(q[:, :, N - 1])
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        graph.replay()
+        lg.lg_sparse_attn_decode_cache(q1, kc, vc, ref_out, ref_lse, ws, N, sink, window, block, stride)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse), rep
+
+
 def test_static_scratch_limit_and_argument_errors_need_no_gpu():
     # checked before the first HIP call (fake, never dereferenced pointers)
     L, P = lg.lib(), 0x1000
