@@ -149,3 +149,44 @@ def test_neighbours_in_the_pack_do_not_matter():
     got = run_varlen([q, k, v, g], cu, sink, window, 1, 0)
     for x, y, name in zip(got, ref, ("out", "lse", "dq", "dk", "dv")):
         assert torch.equal(x[:, a:b], y[:, a:b]), name
+
+
+def test_serving_mix_full_size_sampled():
+    """The pack the benchmark times: eight requests of 2K .. 64K tokens, 32 heads, D=128, sink 64 + window 4096,
+    forward and backward.  The oracle recomputes sampled query rows (out, lse, dq) and sampled keys (dk, dv) of
+    single heads on the sequence alone: the start of the longest request with its sink keys (seen by 65536 rows),
+    where a request's window starts to slide, steady state in a request in the middle of the pack, a request
+    shorter than the window, and the last rows of the pack."""
+    lens = [2048, 4096, 8192, 12288, 16384, 24576, 32768, 65536]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(int).tolist()
+    H, D, sink, window, T = 32, 128, 64, 4096, cu[-1]
+    q, k, v, g = (t[0] for t in lg_synth.prefill_inputs(1, H, H, T, D, 20241012, torch.bfloat16, with_dout=True,
+                                                        device=DEV))
+    out = torch.empty_like(q)
+    lse = torch.empty(H, T, dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd_varlen(q, k, v, out, lse, cu, sink, window)
+    ws = torch.empty(lg.bwd_varlen_workspace_bytes(cu, H, H, D, sink, window, 1, 0, lg.LG_BF16), dtype=torch.uint8,
+                     device=DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lg.lg_sparse_attn_bwd_varlen(q, k, v, out, lse, g, dq, dk, dv, ws, cu, sink, window)
+    torch.cuda.synchronize()
+    for t in (out, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    tol, rel = TOL_OUT[torch.bfloat16], TOL_REL[torch.bfloat16]
+    for h, s, rows, keys in ((0, 7, (0, 40), (0, 40)),                       # longest request: first rows, sink keys
+                             (5, 7, (4080, 4120), (4140, 4180)),             # its window starts to slide
+                             (13, 5, (20001, 20041), (15000, 15040)),        # steady state, a request inside the pack
+                             (21, 0, (2008, 2048), (1000, 1040)),            # a request shorter than the window
+                             (31, 7, (65496, 65536), (65496, 65536))):       # the last rows of the pack
+        print("head", h, "sequence", s, "rows", rows, "keys", keys, flush=True)
+        a0, a1 = cu[s], cu[s + 1]
+        a = [f32np(x[h:h + 1, a0:a1])[None] for x in (q, k, v, g)]
+        w = O.bwd(*a, sink, window, rows=rows, keys=keys)
+        al = dq_delta_allowance(a[0], a[1], a[3], w["out"], sink, window, rows=rows)
+        tag = "serving mix h%d seq%d " % (h, s)
+        r0, r1, k0, k1 = rows[0], rows[1], keys[0], keys[1]
+        assert_close(f32np(dq[h, a0 + r0:a0 + r1]), w["dq"][0, 0, r0:r1], tol, rel, tag + "dq", allow=al[0, 0, r0:r1])
+        assert_close(f32np(dk[h, a0 + k0:a0 + k1]), w["dk"][0, 0, k0:k1], tol, rel, tag + "dk")
+        assert_close(f32np(dv[h, a0 + k0:a0 + k1]), w["dv"][0, 0, k0:k1], tol, rel, tag + "dv")
+        assert_close(f32np(out[h, a0 + r0:a0 + r1]), w["out"][0, 0, r0:r1], tol, rel, tag + "out")
+        assert_close(f32np(lse[h, a0 + r0:a0 + r1]), w["lse"][0, 0, r0:r1], TOL_LSE[torch.bfloat16], None, tag + "lse")
