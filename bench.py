@@ -283,21 +283,12 @@ def main():
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ prefill of a batch of different lengths
-    # (the serving setting): eight requests of 2K .. 64K tokens packed per head, one forward call, beside the
-    # same requests padded to the longest in a [8, H, 65536, D] batch
+    # (the serving setting): requests packed per head, one forward call, beside the same requests padded to
+    # the longest in a [requests, H, longest, D] batch.  Two mixes: eight long requests (2K .. 64K tokens) and
+    # 256 short ones (256 .. 2048 tokens, seeded).
     varlen = None
     if not args.no_extras:
-        lens = [2048, 4096, 8192, 12288, 16384, 24576, 32768, 65536]
-        cu = [0]
-        for n in lens:
-            cu.append(cu[-1] + n)
-        T = cu[-1]
-        vq, vk, vv = (t[0] for t in lg_synth.prefill_inputs(1, H, H, T, D, 20241012, torch.bfloat16, device=dev))
-        vo = torch.empty_like(vq)
-        vl = torch.empty(H, T, dtype=torch.float32, device=dev)
-        pq, pk, pv = lg_synth.prefill_inputs(len(lens), H, H, max(lens), D, 20241013, torch.bfloat16, device=dev)
-        po = torch.empty_like(pq)
-        pl = torch.empty(len(lens), H, max(lens), dtype=torch.float32, device=dev)
+        import numpy as np
 
         def timed_ms(fn, reps=5):
             for _ in range(2):
@@ -311,18 +302,36 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / reps
 
-        v_ms = timed_ms(lambda: lg.lg_sparse_attn_fwd_varlen(vq, vk, vv, vo, vl, cu, sink, window))
-        p_ms = timed_ms(lambda: lg.lg_sparse_attn_fwd(pq, pk, pv, po, pl, sink, window))
-        vfl = 4.0 * D * H * sum(live_pairs(n, sink, window) for n in lens)
-        varlen = {"workload": "prefill forward of 8 requests of %s tokens, H32/32 D128 bf16, sink 64 + window 4096, "
-                              "packed per head (lg_sparse_attn_fwd_varlen)" % lens,
-                  "tokens": T, "fwd_ms": round(v_ms, 3), "flops": vfl,
-                  "tflops": round(vfl / (v_ms * 1e-3) / 1e12, 1),
-                  "frac": round(vfl / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                  "padded_batch_fwd_ms": round(p_ms, 3), "padded_tokens": len(lens) * max(lens),
-                  "speedup_vs_padded": round(p_ms / v_ms, 2)}
-        del vq, vk, vv, vo, vl, pq, pk, pv, po, pl
-        torch.cuda.empty_cache()
+        def varlen_case(what, lens, seed):
+            cu = [0]
+            for n in lens:
+                cu.append(cu[-1] + n)
+            T = cu[-1]
+            vq, vk, vv = (t[0] for t in lg_synth.prefill_inputs(1, H, H, T, D, seed, torch.bfloat16, device=dev))
+            vo = torch.empty_like(vq)
+            vl = torch.empty(H, T, dtype=torch.float32, device=dev)
+            pq, pk, pv = lg_synth.prefill_inputs(len(lens), H, H, max(lens), D, seed + 1, torch.bfloat16, device=dev)
+            po = torch.empty_like(pq)
+            pl = torch.empty(len(lens), H, max(lens), dtype=torch.float32, device=dev)
+            v_ms = timed_ms(lambda: lg.lg_sparse_attn_fwd_varlen(vq, vk, vv, vo, vl, cu, sink, window))
+            p_ms = timed_ms(lambda: lg.lg_sparse_attn_fwd(pq, pk, pv, po, pl, sink, window))
+            vfl = 4.0 * D * H * sum(live_pairs(n, sink, window) for n in lens)
+            rec = {"workload": "prefill forward of %s, H32/32 D128 bf16, sink 64 + window 4096, packed per head "
+                               "(lg_sparse_attn_fwd_varlen)" % what,
+                   "requests": len(lens), "tokens": T, "fwd_ms": round(v_ms, 3), "flops": vfl,
+                   "tflops": round(vfl / (v_ms * 1e-3) / 1e12, 1),
+                   "frac": round(vfl / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                   "padded_batch_fwd_ms": round(p_ms, 3), "padded_tokens": len(lens) * max(lens),
+                   "speedup_vs_padded": round(p_ms / v_ms, 2)}
+            del vq, vk, vv, vo, vl, pq, pk, pv, po, pl
+            torch.cuda.empty_cache()
+            return rec
+
+        long_mix = [2048, 4096, 8192, 12288, 16384, 24576, 32768, 65536]
+        short_mix = [int(x) for x in np.random.default_rng(20241014).integers(256, 2049, 256)]
+        varlen = [varlen_case("8 requests of %s tokens" % long_mix, long_mix, 20241012),
+                  varlen_case("256 requests of 256 .. 2048 tokens (seeded, %d in all)" % sum(short_mix), short_mix,
+                              20241015)]
 
     # ------------------------------------------------------------------ decode, ring cache
     dB, dH, dsink, dwin, dN = 16, 32, 64, 4096, 131072

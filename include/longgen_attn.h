@@ -164,9 +164,11 @@ int lg_debug_bwd_kernel_ms(const void* q, const void* k, const void* v, const vo
  * the results of sequence s equal lg_sparse_attn_fwd / lg_sparse_attn_bwd with B = 1 and
  * N = its length on its rows (bit for bit on the paths those calls reproduce bit for bit).
  * Empty sequences are allowed and skipped; when all are empty nothing is enqueued.
- * One set of launches per sequence goes to hip_stream in order, each at the sequence's own
- * length, so no work is spent on padding; the launches of short sequences (under ~64K query
- * rows x heads) do not fill the GPU, which this entry point does not hide.
+ * No work is spent on padding.  The bf16 forward puts up to 128 sequences into one launch (every
+ * (sequence, head, 256-row query tile) is a workgroup of the same grid, so short sequences fill the GPU
+ * together; each sequence's pattern is cut to its length on the device).  The float32 forward and the
+ * backward enqueue one set of launches per sequence, in order, each at the sequence's own length: there
+ * the launches of short sequences (under ~64K query rows x heads) do not fill the GPU.
  * The backward workspace is shared by the sequences (size = the largest any of them needs; the
  * remarks on lg_sparse_attn_bwd's workspace apply).
  * Errors, beyond the common ones: LG_ERR_NULL for cu_seqlens == NULL; LG_ERR_INVALID_ARG for
@@ -349,6 +351,16 @@ int lg_debug_tile_map(int N, int sink, int window, int block, int stride, int dt
  */
 int lg_debug_tile_walk(int N, int sink, int window, int block, int stride, int transposed, int row,
                        int32_t* order, size_t cap, size_t* count);
+
+/*
+ * Host-only: the pattern as the kernels hold it for a sequence of n tokens, derived from the pattern made for
+ * n_made_for >= n tokens (the packed different-lengths forward makes ONE pattern for a length no sequence
+ * exceeds and derives each sequence's own on the device; sink, window and the strided columns are cut to the
+ * sequence's length).  fields: HOST array of 9 entries = {n, sink, window, max(block, 1), stride, sink blocks,
+ * window blocks, log2(block) or -1, stride - 1 if a power of two else -1}, after the cut.  With
+ * n == n_made_for: the pattern made directly for n.  Runs the same source the kernels compile.
+ */
+int lg_debug_pattern_fields(int n_made_for, int n, int sink, int window, int block, int stride, int32_t* fields);
 
 /*
  * Host-only: the per-lane register mask the bf16 kernels apply on a PARTIAL tile (a tile with live and

@@ -81,6 +81,8 @@ def lib():
         L.lg_debug_tile_walk.restype = _i
         L.lg_debug_partial_tile_bits.argtypes = [_i] * 9 + [ctypes.POINTER(ctypes.c_uint32)]
         L.lg_debug_partial_tile_bits.restype = _i
+        L.lg_debug_pattern_fields.argtypes = [_i] * 6 + [ctypes.POINTER(ctypes.c_int32)]
+        L.lg_debug_pattern_fields.restype = _i
         L.lg_debug_tile_map.argtypes = [_i] * 7 + [ctypes.POINTER(_i), ctypes.POINTER(_i), _vp, _sz,
                                                    _vp, _vp, _sz, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
         L.lg_debug_tile_map.restype = _i
@@ -240,6 +242,16 @@ def lg_sparse_attn_bwd_varlen(q, k, v, out, lse, dout, dq, dk, dv, workspace, cu
                                          _stream(q))
     if st != 0:
         raise LgError(st, "lg_sparse_attn_bwd_varlen")
+
+
+def lg_debug_pattern_fields(n_made_for, n, sink, window, block=1, stride=0):
+    """The 9 pattern fields the kernels hold for a sequence of n tokens, derived from the pattern made for
+    n_made_for tokens (host-only)."""
+    f = (ctypes.c_int32 * 9)()
+    st = lib().lg_debug_pattern_fields(n_made_for, n, sink, window, block, stride, f)
+    if st != 0:
+        raise LgError(st, "lg_debug_pattern_fields")
+    return [int(x) for x in f]
 
 
 def decode_workspace_bytes(B, Hq, Hkv, N, D, sink, window, dtype):

@@ -190,6 +190,28 @@ int lg_sparse_attn_fwd_varlen(const void* q, const void* k, const void* v, void*
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
     return LG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (dtype == LG_BF16) {
+    // one launch per LG_PACK_MAX sequences: every (sequence, head, query tile) is a workgroup of the same
+    // grid, so short sequences fill the GPU together
+    const LgShape sh = make_shape(1, Hq, Hkv, longest > 0 ? longest : 1, D, scale);
+    LgMask tmpl = lg_make_mask(1 << 30, sink, window, block, stride);  // nothing clamped to a length yet
+    tmpl.ld = T;  // a head's rows of all sequences lie side by side
+    int x = 0;
+    while (x < num_seqs) {
+      LgPack pack;
+      pack.n = 0;
+      for (; x < num_seqs && pack.n < LG_PACK_MAX; ++x) {
+        if (cu_seqlens[x + 1] == cu_seqlens[x]) continue;
+        pack.row0[pack.n] = cu_seqlens[x];
+        pack.row0[pack.n + 1] = cu_seqlens[x + 1];  // the next sequence starts here unless empty ones intervene
+        ++pack.n;
+      }
+      if (pack.n == 0) break;
+      if (lg_fwd_bf16_pack_tiles(&pack) < 1) return LG_ERR_INVALID_ARG;
+      if (lg_launch_fwd_bf16_pack(q, k, v, out, lse, sh, tmpl, pack, s) != hipSuccess) return LG_ERR_LAUNCH;
+    }
+    return LG_OK;
+  }
   const size_t es = dtype == LG_F32 ? 4 : 2;
   for (int x = 0; x < num_seqs; ++x) {
     const int n = cu_seqlens[x + 1] - cu_seqlens[x];
@@ -544,6 +566,18 @@ int lg_debug_partial_tile_bits(int N, int sink, int window, int block, int strid
     return LG_ERR_INVALID_ARG;
   const LgMask m = lg_make_mask(N, sink, window, block, stride);
   *bits = transposed ? lg_row_bits(m, fixed, tile0, half) : lg_key_bits(m, fixed, tile0, half);
+  return LG_OK;
+}
+
+int lg_debug_pattern_fields(int n_made_for, int n, int sink, int window, int block, int stride, int32_t* fields) {
+  if (!fields) return LG_ERR_NULL;
+  int st = check_common(1, 1, 1, n_made_for, 64, sink, window, block, stride, LG_BF16);
+  if (st != LG_OK) return st;
+  if (n < 1 || n > n_made_for) return LG_ERR_INVALID_ARG;
+  const LgMask t = lg_make_mask(n_made_for, sink, window, block, stride);
+  const LgMask m = n == n_made_for ? t : lg_mask_for_length(t, n);
+  const int f[9] = {m.N, m.sink, m.window, m.b, m.stride, m.sb, m.wb, m.bshift, m.smask};
+  for (int x = 0; x < 9; ++x) fields[x] = f[x];
   return LG_OK;
 }
 

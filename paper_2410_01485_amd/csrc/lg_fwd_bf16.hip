@@ -27,14 +27,18 @@ static_assert(TQ == 256 && TK == 64, "8 waves x 32 rows, 64-key tiles");
 // TOKEN: the pattern is token-granular without strided columns (block <= 1, stride 0).  The
 // mask fields that are then known let the compiler drop the block / stride arithmetic from
 // the per-tile scheduler, and partial tiles are masked with two compares per element.
-template <int D, bool TOKEN>
+// PackT: LgNoPack for the batch layout (every (b, head) has nqt query tiles of one length), LgPack for
+// sequences of different lengths side by side in each head (nqt = all their query tiles; B = 1).
+struct LgNoPack {};
+template <int D, bool TOKEN, typename PackT>
 __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict__ q,
                                                       const uint16_t* __restrict__ k,
                                                       const uint16_t* __restrict__ v,
                                                       uint16_t* __restrict__ out,
                                                       float* __restrict__ lse, int Hq, int Hkv,
                                                       float scale_log2e, LgMask m_in, int nqt,
-                                                      int total, int per_xcd) {
+                                                      int total, int per_xcd, PackT pack) {
+  constexpr bool PACK = !__is_same(PackT, LgNoPack);
   LgMask m = m_in;
   if (TOKEN) {
     m.b = 1;
@@ -61,19 +65,32 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
   // heads of the GQA group: the G workgroups that walk the same K/V tiles run side by side
   const int G = Hq / Hkv;
   const int gq = L % G, rest = L / G;
-  const int qt = nqt - 1 - (rest % nqt);
+  int qt = nqt - 1 - (rest % nqt);
   const int bhk = rest / nqt;
   const int b = bhk / Hkv, hk = bhk % Hkv;
   const int hq = hk * G + gq;
+  int seq_row0 = 0;  // first row of the sequence inside its head
+  if constexpr (PACK) {
+    // the sequence that owns query tile qt of the launch: the last one whose first tile is <= qt
+    int lo = 0, hi = pack.n;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pack.tile0[mid] <= qt) lo = mid;
+      else hi = mid;
+    }
+    qt -= pack.tile0[lo];
+    seq_row0 = pack.row0[lo];
+    m = lg_mask_for_length(m, pack.row0[lo + 1] - seq_row0);
+  }
   const int N = m.N;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int q0 = qt * TQ;
   const int q1 = min(q0 + TQ - 1, N - 1);
-  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld) * D;
-  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * m.ld) * D;
-  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * m.ld) * D;
+  const size_t qbase = ((size_t)(b * Hq + hq) * m.ld + seq_row0) * D;
+  const uint16_t* kh = k + ((size_t)(b * Hkv + hk) * m.ld + seq_row0) * D;
+  const uint16_t* vh = v + ((size_t)(b * Hkv + hk) * m.ld + seq_row0) * D;
   const int i = q0 + wave * 32 + n;  // this lane's query row
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int qw0 = min(q0 + wave_s * 32, N - 1), qw1 = min(q0 + wave_s * 32 + 31, N - 1);  // this wave's rows
@@ -276,7 +293,7 @@ __global__ __launch_bounds__(NT) void fwd_bf16_kernel(const uint16_t* __restrict
         *reinterpret_cast<uint2*>(orow + db * 32 + 8 * r4) = w;
       }
     if (lse != nullptr && g == 0)
-      lse[(size_t)(b * Hq + hq) * m.ld + i] = (mref * scale_log2e + log2f(l)) * 0.69314718055994530942f;
+      lse[(size_t)(b * Hq + hq) * m.ld + seq_row0 + i] = (mref * scale_log2e + log2f(l)) * 0.69314718055994530942f;
   }
 }
 
@@ -292,10 +309,46 @@ hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void*
   const float sl2 = sh.scale * 1.44269504088896340736f;
   const dim3 grid(per_xcd * 8);
   const bool token = m.b == 1 && m.stride == 0;
-#define LG_FWD_LAUNCH(DD, TT)                                                                     \
-  fwd_bf16_kernel<DD, TT><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k,             \
-                                              (const uint16_t*)v, (uint16_t*)out, lse, sh.Hq,     \
-                                              sh.Hkv, sl2, m, nqt, total, per_xcd)
+#define LG_FWD_LAUNCH(DD, TT)                                                                            \
+  fwd_bf16_kernel<DD, TT, LgNoPack><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k,          \
+                                                        (const uint16_t*)v, (uint16_t*)out, lse, sh.Hq,  \
+                                                        sh.Hkv, sl2, m, nqt, total, per_xcd, LgNoPack{})
+  if (sh.D == 64) {
+    if (token) LG_FWD_LAUNCH(64, true);
+    else LG_FWD_LAUNCH(64, false);
+  } else {
+    if (token) LG_FWD_LAUNCH(128, true);
+    else LG_FWD_LAUNCH(128, false);
+  }
+#undef LG_FWD_LAUNCH
+  return hipGetLastError();
+}
+
+long long lg_fwd_bf16_pack_tiles(LgPack* pack) {
+  long long t = 0;
+  for (int x = 0; x < pack->n; ++x) {
+    pack->tile0[x] = (int)t;
+    t += (pack->row0[x + 1] - pack->row0[x] + TQ - 1) / TQ;
+    if (t > 0x7fffffffLL) return -1;
+  }
+  pack->tile0[pack->n] = (int)t;
+  return t;
+}
+
+hipError_t lg_launch_fwd_bf16_pack(const void* q, const void* k, const void* v, void* out, float* lse,
+                                   const LgShape& sh, const LgMask& tmpl, const LgPack& pack, hipStream_t s) {
+  const int nqt = pack.tile0[pack.n];
+  const long long total_ll = (long long)nqt * sh.Hq;
+  if (nqt < 1 || total_ll > 0x7fffffffLL - 8) return hipErrorInvalidValue;
+  const int total = (int)total_ll;
+  const int per_xcd = (total + 7) / 8;
+  const float sl2 = sh.scale * 1.44269504088896340736f;
+  const dim3 grid(per_xcd * 8);
+  const bool token = tmpl.b == 1 && tmpl.stride == 0;
+#define LG_FWD_LAUNCH(DD, TT)                                                                          \
+  fwd_bf16_kernel<DD, TT, LgPack><<<grid, NT, 0, s>>>((const uint16_t*)q, (const uint16_t*)k,          \
+                                                      (const uint16_t*)v, (uint16_t*)out, lse, sh.Hq,  \
+                                                      sh.Hkv, sl2, tmpl, nqt, total, per_xcd, pack)
   if (sh.D == 64) {
     if (token) LG_FWD_LAUNCH(64, true);
     else LG_FWD_LAUNCH(64, false);

@@ -30,6 +30,21 @@ hipError_t lg_launch_fwd_f32(const float* q, const float* k, const float* v, flo
 hipError_t lg_launch_fwd_bf16(const void* q, const void* k, const void* v, void* out, float* lse,
                               const LgShape& sh, const LgMask& m, hipStream_t s);
 
+// Several sequences of different lengths, packed along the token axis of every head, in ONE forward launch:
+// sequence x owns rows row0[x] .. row0[x+1]-1 of each head and the launch's query tiles tile0[x] .. tile0[x+1]-1.
+// Passed to the kernel by value (about 1 KB of kernel arguments).
+enum { LG_PACK_MAX = 128 };
+struct LgPack {
+  int n;                        // sequences, 1 .. LG_PACK_MAX, none of them empty
+  int row0[LG_PACK_MAX + 1];
+  int tile0[LG_PACK_MAX + 1];
+};
+// Fills tile0 from row0 (bf16 forward tile size); returns the number of query tiles.
+long long lg_fwd_bf16_pack_tiles(LgPack* pack);
+// sh: B = 1, N unused; tmpl: the pattern made for a length no sequence exceeds, ld = rows per head.
+hipError_t lg_launch_fwd_bf16_pack(const void* q, const void* k, const void* v, void* out, float* lse,
+                                   const LgShape& sh, const LgMask& tmpl, const LgPack& pack, hipStream_t s);
+
 // delta_i = dsign * <dout_i, out_i> for rows = B*Hq*N rows of D elements of either dtype;
 // lse2 (may be NULL) = lse * lscale.  delta and lse2 are dense; in dout, out and lse a head's N rows are
 // followed by the next head's after ld rows.

@@ -66,6 +66,24 @@ LG_HD LgMask lg_make_mask(int N, int sink, int window, int block, int stride) {
 // x / b for x >= 0
 LG_HD int lg_div_b(const LgMask& m, int x) { return m.bshift >= 0 ? (x >> m.bshift) : x / m.b; }
 
+// The pattern of a sequence of n tokens that shares sink, window, block and stride with t, a mask made
+// by lg_make_mask for a length that no sequence exceeds: the same fields lg_make_mask(n, ...) gives
+// (it clamps sink, window and stride to the length), ld kept.
+LG_HD LgMask lg_mask_for_length(const LgMask& t, int n) {
+  LgMask m = t;
+  m.N = n;
+  const int nb = lg_div_b(t, n + t.b - 1);
+  m.sb = t.sb < nb ? t.sb : nb;
+  m.wb = t.wb < nb ? t.wb : nb;
+  m.sink = m.sb * t.b;
+  m.window = m.wb * t.b;
+  if (!(t.stride > 0 && t.stride - 1 < nb)) {
+    m.stride = 0;
+    m.smask = -1;
+  }
+  return m;
+}
+
 // Is block column kb one of the strided columns (kb % stride == stride - 1)?  stride > 0.
 LG_HD bool lg_strided(const LgMask& m, int kb) {
   return m.smask >= 0 ? ((kb & m.smask) == m.smask) : (kb % m.stride == m.stride - 1);

@@ -122,6 +122,42 @@ def test_ragged_pack_patterns(dtype, lens, sink, window, block, stride):
     check_pack(lens, 2, 1, 128, sink, window, block, stride, dtype, 402)
 
 
+@pytest.mark.parametrize("D,sink,window,block,stride", [(128, 16, 100, 1, 0), (64, 64, 128, 64, 2)])
+def test_many_short_sequences_in_shared_launches(D, sink, window, block, stride):
+    """300 requests of 0 .. 400 tokens: the bf16 forward puts up to 128 sequences into one launch (every
+    (sequence, head, query tile) a workgroup of the same grid) and derives each sequence's pattern on the device.
+    Every sequence against the oracle on it alone; a sample of them bit for bit against the fixed-length call."""
+    rng = np.random.default_rng(405)
+    lens = [int(x) for x in rng.integers(0, 401, 300)]
+    lens[7] = lens[130] = lens[299] = 0
+    lens[128] = 1
+    Hq, Hkv, dt = 4, 2, torch.bfloat16
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(int).tolist()
+    T = cu[-1]
+    q, k, v = (t[0] for t in lg_synth.prefill_inputs(1, Hq, Hkv, T, D, 406, dt, device=DEV))
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((Hq, T), float("nan"), dtype=torch.float32, device=DEV)
+    lg.lg_sparse_attn_fwd_varlen(q, k, v, out, lse, cu, sink, window, block, stride)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out.float()).any() and not torch.isnan(lse).any()
+    qn, kn, vn, on, ln = (f32np(t) for t in (q, k, v, out, lse))
+    for s, n in enumerate(lens):
+        if n == 0:
+            continue
+        a, b = cu[s], cu[s + 1]
+        wo, wl = O.fwd(qn[None, :, a:b], kn[None, :, a:b], vn[None, :, a:b], sink, window, block, stride)
+        tag = "short sequence %d (n=%d) D%d s%d w%d b%d st%d" % (s, n, D, sink, window, block, stride)
+        assert_close(on[None, :, a:b], wo, TOL_OUT[dt], TOL_REL[dt], tag + " out")
+        assert_close(ln[None, :, a:b], wl, TOL_LSE[dt], None, tag + " lse")
+        if s % 37 == 0 or s in (127, 128, 129, 298):
+            o1 = torch.empty(1, Hq, n, D, dtype=dt, device=DEV)
+            l1 = torch.empty(1, Hq, n, dtype=torch.float32, device=DEV)
+            lg.lg_sparse_attn_fwd(q[None, :, a:b].contiguous(), k[None, :, a:b].contiguous(),
+                                  v[None, :, a:b].contiguous(), o1, l1, sink, window, block, stride)
+            torch.cuda.synchronize()
+            assert torch.equal(o1[0], out[:, a:b]) and torch.equal(l1[0], lse[:, a:b]), tag
+
+
 def test_long_sequences_take_the_resident_kernels():
     """Head dim 128, window 4096: the sequences of 5000 and 9000 tokens run the 64-rows-per-wave backward
     kernels (one resident workgroup per CU, work queue in the shared workspace, cleared per sequence), the

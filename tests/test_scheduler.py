@@ -155,3 +155,30 @@ def test_partial_tile_bits_argument_errors():
         lg.lg_debug_partial_tile_bits(100, 0, 8, 1, 0, 0, 100, 0, 0)      # row outside the sequence
     with pytest.raises(lg.LgError):
         lg.lg_debug_partial_tile_bits(100, 0, 8, 1, 0, 0, 5, 0, 2)        # half is 0 or 1
+
+
+def test_pattern_of_a_packed_sequence_equals_the_pattern_made_for_its_length():
+    """The packed different-lengths forward makes one pattern for a length no sequence exceeds and derives each
+    sequence's own on the device: the derived fields equal those made directly for the sequence's length, and both
+    equal what the mask's definition says (sink, window and strided columns cut to the sequence: values beyond it
+    change nothing)."""
+    rng = np.random.default_rng(11)
+    cases = [(1, 0, 1, 1, 0), (5, 64, 4096, 1, 0), (100, 64, 2048, 64, 64), (4096, 64, 2048, 64, 64), (4097, 64, 2048, 64, 64),
+             (63 * 64, 64, 192, 64, 64), (63 * 64 + 1, 64, 192, 64, 64), (1000, 48, 96, 48, 3), (777, 3, 10, 1, 7), (6, 3, 10, 1, 7),
+             (7, 3, 10, 1, 7), (130, 0, 16, 16, 1)]
+    for _ in range(300):
+        b = int(rng.choice([1, 1, 2, 16, 48, 64]))
+        cases.append((int(rng.integers(1, 5000)), b * int(rng.integers(0, 6)), b * int(rng.integers(1, 40)), b,
+                      int(rng.choice([0, 0, 1, 2, 3, 8, 64]))))
+    for n, sink, window, block, stride in cases:
+        direct = lg.lg_debug_pattern_fields(n, n, sink, window, block, stride)
+        for made_for in (1 << 30, n + 1, 2 * n + 77):
+            assert lg.lg_debug_pattern_fields(made_for, n, sink, window, block, stride) == direct, (n, sink, window, block, stride)
+        b = max(block, 1)
+        nb = -(-n // b)
+        sb, wb = min(sink // b, nb), min(window // b, nb)
+        st = stride if (stride > 0 and stride - 1 < nb) else 0
+        log2 = lambda x: int(np.log2(x)) if x > 0 and (x & (x - 1)) == 0 else -1
+        assert direct == [n, sb * b, wb * b, b, st, sb, wb, log2(b), st - 1 if st > 0 and log2(st) >= 0 else -1]
+    with pytest.raises(lg.LgError):
+        lg.lg_debug_pattern_fields(100, 101, 0, 8, 1, 0)
